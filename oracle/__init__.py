@@ -1,0 +1,218 @@
+"""CPU oracle of the SageAttention2++ "8+8" forward pass -- TEST INFRASTRUCTURE.
+
+A thin numpy/ctypes front for ``sage_oracle.c`` (plain C, double precision).
+Only the test-suite, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package; the GPU library never does, and this
+package imports nothing of the GPU library.  The passages of the paper each
+routine follows are cited in the C source.
+
+Parity status of the pins (see tests/test_oracle_*.py): every routine here is
+pinned by brute force, closed forms or an independent library rounding; the
+only figure with no pin is the accuracy *relative to full-precision attention*
+on synthetic data ("parity unpinned": the paper's Table 2 was measured on real
+model activations that are not available; it serves as a plausibility band).
+
+All tensors of one head are C-contiguous ``[N, d]`` numpy arrays.  Inputs are
+``float32`` arrays holding values exactly representable in the 16-bit input
+type (the caller converts).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+# Defaults of the method: Section 3.2 selects P_r = 224 and V_r = 4.5.  Block
+# sizes are this build's reading of "per-block" in Section 2.1.
+P_R = 224.0
+V_R = 4.5
+BQ = 128
+BK = 64
+W = 128
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+            _build.build()
+        lib = ctypes.CDLL(path)
+        c_f, c_d, c_i = ctypes.c_float, ctypes.c_double, ctypes.c_int
+        vp = ctypes.c_void_p
+        lib.sage_oracle_e4m3_decode.restype = c_d
+        lib.sage_oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
+        lib.sage_oracle_e4m3_encode.restype = ctypes.c_uint8
+        lib.sage_oracle_e4m3_encode.argtypes = [c_d]
+        lib.sage_oracle_round16.restype = c_d
+        lib.sage_oracle_round16.argtypes = [c_d, c_i]
+        lib.sage_oracle_k_mean.restype = None
+        lib.sage_oracle_k_mean.argtypes = [vp, c_i, c_i, vp]
+        lib.sage_oracle_quant_int8.restype = None
+        lib.sage_oracle_quant_int8.argtypes = [vp, vp, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_quant_v.restype = None
+        lib.sage_oracle_quant_v.argtypes = [vp, c_i, c_i, c_f, vp, vp]
+        lib.sage_oracle_attn_rows.restype = None
+        lib.sage_oracle_attn_rows.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_d, c_d,
+                                              c_i, c_i, c_i, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_attn_rows_fp.restype = None
+        lib.sage_oracle_attn_rows_fp.argtypes = [vp, vp, vp, c_i, c_i, c_i, c_d, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_num_threads.restype = c_i
+        lib.sage_oracle_num_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().sage_oracle_num_threads())
+
+
+# --------------------------------------------------------------------------
+# number formats
+# --------------------------------------------------------------------------
+def e4m3_decode(codes) -> np.ndarray:
+    lib = _load()
+    table = np.array([lib.sage_oracle_e4m3_decode(i) for i in range(256)], dtype=np.float64)
+    return table[np.asarray(codes, dtype=np.uint8)]
+
+
+def e4m3_encode(x) -> np.ndarray:
+    lib = _load()
+    x = np.asarray(x, dtype=np.float64)
+    out = np.empty(x.shape, dtype=np.uint8)
+    flat_in, flat_out = x.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = lib.sage_oracle_e4m3_encode(float(flat_in[i]))
+    return out
+
+
+def round16(x, dtype: str) -> np.ndarray:
+    lib = _load()
+    code = {"fp16": 0, "bf16": 1}[dtype]
+    x = np.asarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    fi, fo = x.reshape(-1), out.reshape(-1)
+    for i in range(fi.size):
+        fo[i] = lib.sage_oracle_round16(float(fi[i]), code)
+    return out
+
+
+# --------------------------------------------------------------------------
+# quantisation stage (one head)
+# --------------------------------------------------------------------------
+def k_mean(K: np.ndarray) -> np.ndarray:
+    K = _c(K, np.float32)
+    N, d = K.shape
+    mu = np.empty(d, dtype=np.float32)
+    _load().sage_oracle_k_mean(_p(K), N, d, _p(mu))
+    return mu
+
+
+def quant_int8(X: np.ndarray, mu, block: int):
+    """Per-block INT8 codes [N, d] and scales [ceil(N/block)] of X - mu."""
+    X = _c(X, np.float32)
+    N, d = X.shape
+    nb = (N + block - 1) // block
+    codes = np.empty((N, d), dtype=np.int8)
+    delta = np.empty(nb, dtype=np.float32)
+    mu_p = None
+    if mu is not None:
+        mu = _c(mu, np.float32)
+        assert mu.shape == (d,)
+        mu_p = _p(mu)
+    _load().sage_oracle_quant_int8(_p(X), mu_p, N, d, block, _p(codes), _p(delta))
+    return codes, delta
+
+
+def quant_v(V: np.ndarray, v_r: float = V_R):
+    """Per-channel FP8-E4M3 codes [N, d] (token-major) and scales [d]."""
+    V = _c(V, np.float32)
+    N, d = V.shape
+    codes = np.empty((N, d), dtype=np.uint8)
+    delta = np.empty(d, dtype=np.float32)
+    _load().sage_oracle_quant_v(_p(V), N, d, float(v_r), _p(codes), _p(delta))
+    return codes, delta
+
+
+# --------------------------------------------------------------------------
+# attention stage (one head)
+# --------------------------------------------------------------------------
+def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: float = P_R,
+              bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
+              out_dtype="bf16", want_p: bool = False):
+    Qc, Kc = _c(Qc, np.int8), _c(Kc, np.int8)
+    Vc = _c(Vc, np.uint8)
+    dq, dk, dv = _c(dq, np.float32), _c(dk, np.float32), _c(dv, np.float32)
+    N, d = Qc.shape
+    assert Kc.shape == (N, d) and Vc.shape == (N, d) and dv.shape == (d,)
+    assert dq.shape == ((N + bq - 1) // bq,) and dk.shape == ((N + bk - 1) // bk,)
+    assert w % bk == 0 or bk % w == 0
+    row1 = N if row1 is None else row1
+    assert 0 <= row0 <= row1 <= N
+    code = {"fp16": 0, "bf16": 1, None: -1}[out_dtype]
+    out = np.empty((row1 - row0, d), dtype=np.float64)
+    P = np.empty((row1 - row0, N), dtype=np.float64) if want_p else None
+    _load().sage_oracle_attn_rows(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), N, d, int(causal),
+                                  float(sm_scale), float(p_r), bq, bk, w, row0, row1, code,
+                                  _p(out), _p(P) if want_p else None)
+    return (out, P) if want_p else out
+
+
+def attn_rows_fp(Q, K, V, *, causal: bool, sm_scale: float, w: int = W, row0: int = 0, row1=None,
+                 want_p: bool = False):
+    """Block-wise online softmax on unquantised double operands (quantisers off)."""
+    Q, K, V = _c(Q, np.float64), _c(K, np.float64), _c(V, np.float64)
+    N, d = Q.shape
+    row1 = N if row1 is None else row1
+    out = np.empty((row1 - row0, d), dtype=np.float64)
+    P = np.empty((row1 - row0, N), dtype=np.float64) if want_p else None
+    _load().sage_oracle_attn_rows_fp(_p(Q), _p(K), _p(V), N, d, int(causal), float(sm_scale), w,
+                                     row0, row1, _p(out), _p(P) if want_p else None)
+    return (out, P) if want_p else out
+
+
+def quantize_head(q, k, v, *, v_r: float = V_R, bq: int = BQ, bk: int = BK):
+    """Quantisation stage of one head: smoothing statistic, INT8 Q/K, FP8 V."""
+    mu = k_mean(k)
+    q_codes, q_scale = quant_int8(q, None, bq)
+    k_codes, k_scale = quant_int8(k, mu, bk)
+    v_codes, v_scale = quant_v(v, v_r)
+    return dict(k_mean=mu, q_codes=q_codes, q_scale=q_scale, k_codes=k_codes, k_scale=k_scale,
+                v_codes=v_codes, v_scale=v_scale)
+
+
+def sage_attention_head(q, k, v, *, causal: bool, sm_scale: float, out_dtype: str,
+                        p_r: float = P_R, v_r: float = V_R, bq: int = BQ, bk: int = BK, w: int = W,
+                        row0: int = 0, row1=None, quant=None):
+    """Whole path for one head; returns (output rows as float64, quantised operands)."""
+    if quant is None:
+        quant = quantize_head(q, k, v, v_r=v_r, bq=bq, bk=bk)
+    out = attn_rows(quant["q_codes"], quant["k_codes"], quant["v_codes"], quant["q_scale"],
+                    quant["k_scale"], quant["v_scale"], causal=causal, sm_scale=sm_scale, p_r=p_r,
+                    bq=bq, bk=bk, w=w, row0=row0, row1=row1, out_dtype=out_dtype)
+    return out, quant
+
+
+def sage_attention(q, k, v, *, causal: bool, sm_scale: float, out_dtype: str, **kw):
+    """Whole path for a [B, H, N, d] problem (small sizes only)."""
+    B, H, N, d = q.shape
+    out = np.empty((B, H, N, d), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            out[b, h], _ = sage_attention_head(q[b, h], k[b, h], v[b, h], causal=causal,
+                                               sm_scale=sm_scale, out_dtype=out_dtype, **kw)
+    return out

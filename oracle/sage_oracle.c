@@ -1,0 +1,375 @@
+/*
+ * CPU oracle for the SageAttention2++ "8+8" attention forward pass
+ * (INT8 Q.K^T, FP8-E4M3 P.V).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, double-precision
+ * statement of what the method computes, written from the paper so that a
+ * reader can check it against the text by eye.  It shares no code with the
+ * GPU library, is never linked into it and must never be reached from the
+ * product path: only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call it.
+ *
+ * What each routine follows (all references are to the paper):
+ *   - tiling of Q, K, P~, V into blocks and the online softmax: Section 2.1;
+ *   - per-block INT8 scales  delta_Q = max|Q|/127, delta_K = max|K|/127,
+ *     per-channel FP8 scale  delta_V = colmax|V| / V_r,  the rounding
+ *     X^ = round(X / delta)  and the de-quantisation
+ *     PV = P^ V^ * delta_P * delta_V: Section 2.1 and Section 3.1, Eq. (2);
+ *   - narrowed FP8 ranges P_r, V_r (defaults 224 and 4.5): Section 3.1-3.2;
+ *   - smoothing of K (subtracting the per-channel mean over tokens):
+ *     Section 3, first paragraph (the paper names the step, gives no formula;
+ *     the per-(batch, head, channel) mean over all N tokens is the reading
+ *     taken here);
+ *   - accuracy metrics are NOT here (they are measurement, not method).
+ *
+ * Readings taken where the paper is silent (listed again in the design notes):
+ *   round(.) is round-to-nearest-even everywhere; max(|.|) is used for every
+ *   scale; delta_P is the constant 1/P_r (P~ <= 1 by construction); the softmax
+ *   denominator l accumulates the UNQUANTISED P~; exponentials are base 2 with
+ *   sm_scale*log2(e) folded into the de-quantisation constant; causal means key
+ *   n is visible to query r iff n <= r; partial blocks take their scale over the
+ *   valid rows only; an all-zero block or channel gets scale 0 and codes 0; the
+ *   output is rounded (RNE) to the 16-bit input type.
+ *
+ * Steps that are *defined* as IEEE binary32 operations (so that "bit-exact
+ * codes and scales" is a meaningful requirement) are evaluated in `float`
+ * with contraction disabled (compile with -ffp-contract=off): the channel
+ * mean's final rounding, K - mean, scale = a/range, r = range/a, x*r.
+ * Everything else is double.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define SAGE_ORACLE_LOG2E 1.4426950408889634073599246810019
+
+/* --------------------------------------------------------------------- */
+/* number formats                                                        */
+/* --------------------------------------------------------------------- */
+
+/* FP8 E4M3 in the OCP "FN" flavour (Section 3.1 quotes its range, +-448):
+ * 1 sign, 4 exponent (bias 7), 3 mantissa bits; no infinities; exponent 15
+ * with mantissa 7 is NaN; exponent 0 is subnormal with step 2^-9.            */
+double sage_oracle_e4m3_decode(uint8_t code)
+{
+    int sign = code >> 7;
+    int e = (code >> 3) & 15;
+    int m = code & 7;
+    double mag;
+    if (e == 15 && m == 7)
+        return NAN;
+    if (e == 0)
+        mag = ldexp((double)m, -9);          /* m/8 * 2^-6 */
+    else
+        mag = ldexp((double)(8 + m), e - 10); /* (1 + m/8) * 2^(e-7) */
+    return sign ? -mag : mag;
+}
+
+/* Round-to-nearest-even encoder from a real number; magnitudes that would
+ * round beyond 448 saturate to 448 (never reached with the default ranges,
+ * Section 3.1).                                                              */
+uint8_t sage_oracle_e4m3_encode(double x)
+{
+    uint8_t sign = signbit(x) ? 0x80 : 0x00;
+    double a = fabs(x);
+    if (isnan(x))
+        return 0x7f;
+    if (a >= 464.0) /* 464 is the midpoint between 448 and the next (absent) step */
+        return sign | 0x7e;
+    if (a < ldexp(1.0, -6)) {
+        /* subnormal range, step 2^-9; a result of 8 steps is the smallest normal */
+        int r = (int)nearbyint(ldexp(a, 9));
+        return sign | (uint8_t)r;
+    }
+    int ex;
+    (void)frexp(a, &ex);            /* a = f * 2^ex, f in [0.5, 1) */
+    int E = ex - 1;                 /* a in [2^E, 2^(E+1)) */
+    int r = (int)nearbyint(ldexp(a, 3 - E)); /* in [8, 16] */
+    if (r == 16) {
+        r = 8;
+        E += 1;
+    }
+    int biased = E + 7;
+    if (biased > 15 || (biased == 15 && r - 8 > 6))
+        return sign | 0x7e;
+    return sign | (uint8_t)((biased << 3) | (r - 8));
+}
+
+/* Round a double to a 16-bit floating type and return the rounded value as a
+ * double.  dtype 0 = IEEE binary16 (fp16), 1 = bfloat16.  RNE, gradual
+ * underflow, overflow to infinity.                                           */
+double sage_oracle_round16(double x, int dtype)
+{
+    int p = dtype == 0 ? 11 : 8;          /* significand bits incl. the hidden one */
+    int emin = dtype == 0 ? -14 : -126;
+    double maxv = dtype == 0 ? 65504.0 : ldexp(255.0, 120); /* (2 - 2^-7) * 2^127 */
+    if (x == 0.0 || isnan(x) || isinf(x))
+        return x;
+    int ex;
+    (void)frexp(fabs(x), &ex);
+    int E = ex - 1;
+    if (E < emin)
+        E = emin;
+    double q = ldexp(1.0, E - (p - 1));
+    double r = nearbyint(x / q) * q;
+    if (fabs(r) > maxv)
+        return x > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/* --------------------------------------------------------------------- */
+/* quantisation stage                                                    */
+/* --------------------------------------------------------------------- */
+
+/* Smoothing statistic (Section 3): mu[c] = mean over the N tokens of K[n][c].
+ * The sum is taken in double, the quotient is rounded once to binary32.      */
+void sage_oracle_k_mean(const float *K, int N, int d, float *mu)
+{
+    for (int c = 0; c < d; ++c) {
+        double s = 0.0;
+        for (int n = 0; n < N; ++n)
+            s += (double)K[(size_t)n * d + c];
+        mu[c] = (float)(s / (double)N);
+    }
+}
+
+/* Per-block INT8 quantisation (Section 2.1): rows are grouped into blocks of
+ * `block` consecutive tokens (the last may be partial); for each block
+ *   a = max|X'|,  delta = a/127,  X^ = round(X' * (127/a)),   X' = X - mu
+ * (mu == NULL means no smoothing, i.e. X' = X).  binary32 operations.        */
+void sage_oracle_quant_int8(const float *X, const float *mu, int N, int d, int block,
+                            int8_t *codes, float *delta)
+{
+    int nb = (N + block - 1) / block;
+    for (int j = 0; j < nb; ++j) {
+        int n0 = j * block;
+        int n1 = n0 + block < N ? n0 + block : N;
+        float a = 0.0f;
+        for (int n = n0; n < n1; ++n)
+            for (int c = 0; c < d; ++c) {
+                float x = X[(size_t)n * d + c];
+                if (mu)
+                    x = x - mu[c];
+                float ax = fabsf(x);
+                if (ax > a)
+                    a = ax;
+            }
+        if (a == 0.0f) {
+            delta[j] = 0.0f;
+            for (int n = n0; n < n1; ++n)
+                memset(codes + (size_t)n * d, 0, (size_t)d);
+            continue;
+        }
+        delta[j] = a / 127.0f;
+        float r = 127.0f / a;
+        for (int n = n0; n < n1; ++n)
+            for (int c = 0; c < d; ++c) {
+                float x = X[(size_t)n * d + c];
+                if (mu)
+                    x = x - mu[c];
+                float y = x * r;
+                codes[(size_t)n * d + c] = (int8_t)nearbyintf(y);
+            }
+    }
+}
+
+/* Per-channel FP8 quantisation of V (Section 2.1 and Eq. (2)):
+ *   a_c = max_n |V[n][c]|,  delta_V[c] = a_c / V_r,  V^ = e4m3(V * (V_r/a_c)).
+ * Codes are returned token-major, codes[n][c].                               */
+void sage_oracle_quant_v(const float *V, int N, int d, float v_r, uint8_t *codes, float *delta)
+{
+    for (int c = 0; c < d; ++c) {
+        float a = 0.0f;
+        for (int n = 0; n < N; ++n) {
+            float ax = fabsf(V[(size_t)n * d + c]);
+            if (ax > a)
+                a = ax;
+        }
+        if (a == 0.0f) {
+            delta[c] = 0.0f;
+            for (int n = 0; n < N; ++n)
+                codes[(size_t)n * d + c] = 0;
+            continue;
+        }
+        delta[c] = a / v_r;
+        float r = v_r / a;
+        for (int n = 0; n < N; ++n) {
+            float y = V[(size_t)n * d + c] * r;
+            codes[(size_t)n * d + c] = sage_oracle_e4m3_encode((double)y);
+        }
+    }
+}
+
+/* --------------------------------------------------------------------- */
+/* attention stage                                                       */
+/* --------------------------------------------------------------------- */
+
+/* Quantised attention for the query rows [row0, row1) of ONE head
+ * (Sections 2.1 and 3.1).  For every row r, key steps of W keys are taken in
+ * ascending order; per step
+ *     x_n   = S_int[r][n] * (delta_Q[r/BQ] * delta_K[n/BK] * sm_scale * log2 e)
+ *     m'    = max(m, max_n x_n)            masked keys count as -inf
+ *     alpha = 2^(m - m')
+ *     P~_n  = 2^(x_n - m')                 masked keys give exactly 0
+ *     l     = alpha*l + sum_n P~_n         (unquantised)
+ *     P^_n  = e4m3(P~_n * P_r)
+ *     acc   = alpha*acc + sum_n P^_n * V^[n][:]
+ * and finally O[r][c] = acc[c] * delta_V[c] / (P_r * l), rounded to `out_dtype`
+ * (0 fp16, 1 bf16, -1 no rounding).  For a causal row the loop stops after
+ * the step that holds key r: later steps are fully masked and change nothing.
+ *
+ * P_out, if not NULL, receives the normalised probabilities 2^(x - m_final)/l
+ * as (row1-row0) x N doubles (test use only: rows must sum to one).          */
+void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc,
+                           const float *dq, const float *dk, const float *dv,
+                           int N, int d, int causal, double sm_scale, double p_r,
+                           int BQ, int BK, int W, int row0, int row1, int out_dtype,
+                           double *out, double *P_out)
+{
+    double *Vd = (double *)malloc((size_t)N * d * sizeof(double));
+    for (size_t i = 0; i < (size_t)N * d; ++i)
+        Vd[i] = sage_oracle_e4m3_decode(Vc[i]);
+
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)W * sizeof(double));
+        double *acc = (double *)malloc((size_t)d * sizeof(double));
+        double *xs = P_out ? (double *)malloc((size_t)N * sizeof(double)) : NULL;
+#pragma omp for schedule(dynamic, 1)
+        for (int r = row0; r < row1; ++r) {
+            const int8_t *qr = Qc + (size_t)r * d;
+            double m = -INFINITY, l = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc[c] = 0.0;
+            int last = causal ? r : N - 1;
+            for (int t0 = 0; t0 <= last; t0 += W) {
+                int t1 = t0 + W < N ? t0 + W : N;
+                double mx = -INFINITY;
+                for (int n = t0; n < t1; ++n) {
+                    if (causal && n > r) {
+                        x[n - t0] = -INFINITY;
+                        continue;
+                    }
+                    const int8_t *kn = Kc + (size_t)n * d;
+                    int32_t s = 0;
+                    for (int c = 0; c < d; ++c)
+                        s += (int32_t)qr[c] * (int32_t)kn[c];
+                    double cst = (double)dq[r / BQ] * (double)dk[n / BK] * sm_scale * SAGE_ORACLE_LOG2E;
+                    x[n - t0] = (double)s * cst;
+                    if (x[n - t0] > mx)
+                        mx = x[n - t0];
+                }
+                double m_new = m > mx ? m : mx;
+                double alpha = exp2(m - m_new); /* m = -inf on the first step gives 0 */
+                l *= alpha;
+                for (int c = 0; c < d; ++c)
+                    acc[c] *= alpha;
+                for (int n = t0; n < t1; ++n) {
+                    double p = isinf(x[n - t0]) ? 0.0 : exp2(x[n - t0] - m_new);
+                    l += p;
+                    double ph = sage_oracle_e4m3_decode(sage_oracle_e4m3_encode(p * p_r));
+                    if (ph != 0.0) {
+                        const double *vn = Vd + (size_t)n * d;
+                        for (int c = 0; c < d; ++c)
+                            acc[c] += ph * vn[c];
+                    }
+                    if (xs)
+                        xs[n] = x[n - t0];
+                }
+                m = m_new;
+            }
+            for (int c = 0; c < d; ++c) {
+                double o = acc[c] * (double)dv[c] / (p_r * l);
+                out[(size_t)(r - row0) * d + c] = out_dtype < 0 ? o : sage_oracle_round16(o, out_dtype);
+            }
+            if (P_out) {
+                double *pr = P_out + (size_t)(r - row0) * N;
+                for (int n = 0; n < N; ++n)
+                    pr[n] = (n <= last && !isinf(xs[n])) ? exp2(xs[n] - m) / l : 0.0;
+            }
+        }
+        free(x);
+        free(acc);
+        free(xs);
+    }
+    free(Vd);
+}
+
+/* The same block-wise online softmax on UNQUANTISED double operands
+ * (Section 2.1 without any quantiser: P^ := P~, all scales 1).  It exists so
+ * that the tiling / online-softmax skeleton can be pinned against the plain
+ * definition softmax(Q K^T * sm_scale) V.                                     */
+void sage_oracle_attn_rows_fp(const double *Q, const double *K, const double *V,
+                              int N, int d, int causal, double sm_scale, int W,
+                              int row0, int row1, double *out, double *P_out)
+{
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)W * sizeof(double));
+        double *acc = (double *)malloc((size_t)d * sizeof(double));
+        double *xs = P_out ? (double *)malloc((size_t)N * sizeof(double)) : NULL;
+#pragma omp for schedule(dynamic, 1)
+        for (int r = row0; r < row1; ++r) {
+            const double *qr = Q + (size_t)r * d;
+            double m = -INFINITY, l = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc[c] = 0.0;
+            int last = causal ? r : N - 1;
+            for (int t0 = 0; t0 <= last; t0 += W) {
+                int t1 = t0 + W < N ? t0 + W : N;
+                double mx = -INFINITY;
+                for (int n = t0; n < t1; ++n) {
+                    if (causal && n > r) {
+                        x[n - t0] = -INFINITY;
+                        continue;
+                    }
+                    const double *kn = K + (size_t)n * d;
+                    double s = 0.0;
+                    for (int c = 0; c < d; ++c)
+                        s += qr[c] * kn[c];
+                    x[n - t0] = s * sm_scale * SAGE_ORACLE_LOG2E;
+                    if (x[n - t0] > mx)
+                        mx = x[n - t0];
+                }
+                double m_new = m > mx ? m : mx;
+                double alpha = exp2(m - m_new);
+                l *= alpha;
+                for (int c = 0; c < d; ++c)
+                    acc[c] *= alpha;
+                for (int n = t0; n < t1; ++n) {
+                    double p = isinf(x[n - t0]) ? 0.0 : exp2(x[n - t0] - m_new);
+                    l += p;
+                    const double *vn = V + (size_t)n * d;
+                    for (int c = 0; c < d; ++c)
+                        acc[c] += p * vn[c];
+                    if (xs)
+                        xs[n] = x[n - t0];
+                }
+                m = m_new;
+            }
+            for (int c = 0; c < d; ++c)
+                out[(size_t)(r - row0) * d + c] = acc[c] / l;
+            if (P_out) {
+                double *pr = P_out + (size_t)(r - row0) * N;
+                for (int n = 0; n < N; ++n)
+                    pr[n] = (n <= last && !isinf(xs[n])) ? exp2(xs[n] - m) / l : 0.0;
+            }
+        }
+        free(x);
+        free(acc);
+        free(xs);
+    }
+}
+
+int sage_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
