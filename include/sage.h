@@ -1,0 +1,143 @@
+/*
+ * libsage -- SageAttention2++ "8+8" quantised attention forward for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer named "device" is a device (HBM) pointer owned by the
+ * caller; the library allocates nothing, keeps no state, never synchronises
+ * and enqueues all its work on `stream` (a hipStream_t passed as void*;
+ * NULL = the default stream).  Inputs are never modified.
+ *
+ * Tensors.  Q, K, V and the output are contiguous [B, H, N, d] arrays of a
+ * 16-bit floating type (`sage_dtype`), d in {64, 128}, N >= 1 arbitrary
+ * (N_q = N_k = N, H_q = H_kv = H).
+ *
+ * The method (paper sections in brackets):
+ *   stage 1  K is smoothed by subtracting its per-(b,h,channel) mean over the
+ *            N tokens [Sec. 3]; Q and the smoothed K are quantised to INT8 per
+ *            block of SAGE_BQ / SAGE_BK consecutive tokens with scale
+ *            delta = max|X| / 127 [Sec. 2.1]; V is quantised to FP8 E4M3 per
+ *            channel with scale delta_V = max_n|V| / V_r [Sec. 2.1, Eq. 2].
+ *   stage 2  per query block, key steps of SAGE_W keys in ascending order:
+ *            S = Q^ K^T in INT8 with INT32 accumulation, de-quantised by
+ *            delta_Q delta_K, base-2 online softmax, P~ quantised to FP8 E4M3
+ *            as P^ = rne(P~ * P_r), O += P^ V^ in FP8 with FP32 accumulation;
+ *            finally O * delta_V / (P_r * l) [Sec. 2.1, Sec. 3.1].
+ * Rounding is round-to-nearest-even everywhere; each quantiser step is one
+ * IEEE binary32 operation (x - mean, a / range, range / a, x * r), which is
+ * what makes codes and scales reproducible bit for bit.
+ *
+ * Return value of every call: SAGE_OK (0) or a negative error code; nothing
+ * is enqueued when an argument check fails.  No exceptions, no aborts.
+ */
+#ifndef SAGE_H
+#define SAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAGE_BQ 128      /* tokens per Q quantisation block  [Sec. 2.1 "per-block"] */
+#define SAGE_BK 64       /* tokens per K quantisation block  */
+#define SAGE_W 128       /* keys consumed per online-softmax step */
+#define SAGE_VTILE 128   /* keys per tile of the transposed FP8 V layout */
+
+typedef enum { SAGE_F16 = 0, SAGE_BF16 = 1 } sage_dtype;
+
+enum {
+    SAGE_OK = 0,
+    SAGE_EINVAL = -1,     /* NULL pointer, d not in {64,128}, sizes < 1, pointer not 16-byte aligned */
+    SAGE_EWORKSPACE = -2, /* workspace missing or smaller than the matching *_workspace_bytes() */
+    SAGE_EHIP = -3        /* a kernel launch failed; text from sage_strerror() */
+};
+
+typedef struct {
+    int bq, bk, w, v_tile; /* SAGE_BQ, SAGE_BK, SAGE_W, SAGE_VTILE */
+    float p_r, v_r;        /* default FP8 ranges, 224 and 4.5 [Sec. 3.2] */
+} sage_params;
+
+/* Report the fixed blocking and the default ranges.  Host call. */
+int sage_get_params(sage_params *out);
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char *sage_strerror(int code);
+
+/* ---- sizes (host calls, no GPU work) ----------------------------------- */
+
+/* Bytes of the transposed FP8 V buffer: B*H*ceil(N/128)*d*128. */
+size_t sage_v_fp8_bytes(int B, int H, int N, int d);
+/* Scratch needed by sage_quant_qk / sage_quant_v (partial column statistics). */
+size_t sage_quant_workspace_bytes(int B, int H, int N, int d);
+/* Scratch needed by sage_attn_fwd (quantised operands + scales + the above). */
+size_t sage_workspace_bytes(int B, int H, int N, int d);
+
+/* ---- stage 1 ----------------------------------------------------------- */
+
+/*
+ * K smoothing + per-block INT8 quantisation of Q and K  [Sec. 3; Sec. 2.1].
+ *   q, k      device, [B,H,N,d] of `dt`                                  (in)
+ *   q_i8,k_i8 device, [B,H,N,d] int8 codes in [-127,127]                 (out)
+ *   q_scale   device, [B,H,ceil(N/SAGE_BQ)] float, delta_Q               (out)
+ *   k_scale   device, [B,H,ceil(N/SAGE_BK)] float, delta_K               (out)
+ *   k_mean    device, [B,H,d] float, the subtracted mean                 (out)
+ *   workspace device, >= sage_quant_workspace_bytes(), 256-byte aligned (scratch)
+ * mean = float(sum_n K / N) with the sum in double; K' = K - mean;
+ * a = max|K'| over the valid rows of a block; delta = a / 127;
+ * code = rne(K' * (127 / a)); a == 0 gives delta 0 and codes 0.
+ */
+int sage_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8,
+                  float *q_scale, float *k_scale, float *k_mean,
+                  int B, int H, int N, int d, sage_dtype dt, void *stream,
+                  void *workspace, size_t workspace_bytes);
+
+/*
+ * Per-channel FP8 E4M3 quantisation of V  [Sec. 2.1; Sec. 3.1 Eq. 2].
+ *   v        device, [B,H,N,d] of `dt`                                   (in)
+ *   v_fp8    device, sage_v_fp8_bytes() bytes                            (out)
+ *   v_scale  device, [B,H,d] float, delta_V = max_n|V| / v_r             (out)
+ * code = e4m3_rne(V * (v_r / a_c)); a_c == 0 gives delta 0 and codes 0.
+ *
+ * Layout of v_fp8 (private to this library but documented, because the codes
+ * are part of the parity contract): [B*H][T = ceil(N/128)][d][128] bytes; the
+ * 128 bytes of (tile T, channel c) hold the 128 keys of the tile permuted so
+ * that byte 32*g + 4*t + i is key 128*T + 16*t + 4*g + i  (t<8, g<4, i<4);
+ * keys >= N hold code 0.
+ */
+int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r,
+                 int B, int H, int N, int d, sage_dtype dt, void *stream,
+                 void *workspace, size_t workspace_bytes);
+
+/* ---- stage 2 ----------------------------------------------------------- */
+
+/*
+ * Fused attention on already quantised operands  [Sec. 2.1; Sec. 3.1].
+ * Arguments as produced by sage_quant_qk / sage_quant_v (same layouts);
+ *   out      device, [B,H,N,d] of `out_dt`; every element is written     (out)
+ *   causal   0: all keys visible; 1: key n visible to query r iff n <= r;
+ *            key tiles entirely above the diagonal are skipped
+ *   sm_scale softmax scale; <= 0 or NaN selects 1/sqrt(d)
+ *   p_r      FP8 range of P~ (224 by default), must lie in (0, 448]
+ * The running maximum is updated once per SAGE_W keys to the exact step
+ * maximum; l accumulates the unquantised P~.
+ */
+int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8,
+                            const float *q_scale, const float *k_scale, const float *v_scale,
+                            void *out, int B, int H, int N, int d, int causal, float sm_scale,
+                            float p_r, sage_dtype out_dt, void *stream);
+
+/*
+ * The whole forward pass: sage_quant_qk + sage_quant_v + sage_attn_fwd_quantized
+ * with the default ranges (P_r = 224, V_r = 4.5), intermediates in `workspace`
+ * (device, >= sage_workspace_bytes(), 256-byte aligned).
+ *   q, k, v  device, [B,H,N,d] of `dt`                                   (in)
+ *   out      device, [B,H,N,d] of `dt`                                   (out)
+ */
+int sage_attn_fwd(const void *q, const void *k, const void *v, void *out,
+                  int B, int H, int N, int d, int causal, float sm_scale, void *stream,
+                  sage_dtype dt, void *workspace, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGE_H */

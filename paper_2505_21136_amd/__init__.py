@@ -1,0 +1,192 @@
+"""Python binding of libsage (SageAttention2++ 8+8 forward, MI355X / gfx950).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libsage.so`` behind the C ABI declared in ``include/sage.h``.  PyTorch is used
+for device memory and the current stream.  There is no CPU fallback: importing
+works without a GPU (the library loads lazily), but any compute call raises if
+the shared library is missing or fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+__all__ = [
+    "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
+    "sage_quant_qk", "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd", "v_fp8_to_token_major",
+    "EXPORTS",
+]
+
+SAGE_F16, SAGE_BF16 = 0, 1
+EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_workspace_bytes",
+           "sage_workspace_bytes", "sage_quant_qk", "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd"]
+
+
+class SageError(RuntimeError):
+    pass
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("bq", ctypes.c_int), ("bk", ctypes.c_int), ("w", ctypes.c_int), ("v_tile", ctypes.c_int),
+                ("p_r", ctypes.c_float), ("v_r", ctypes.c_float)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library (raises SageError if it has not been built)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            raise SageError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                            "(there is no fallback path)")
+        L = ctypes.CDLL(path)
+        i, f, vp, sz = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+        L.sage_get_params.restype = i
+        L.sage_get_params.argtypes = [ctypes.POINTER(_Params)]
+        L.sage_strerror.restype = ctypes.c_char_p
+        L.sage_strerror.argtypes = [i]
+        for name in ("sage_v_fp8_bytes", "sage_quant_workspace_bytes", "sage_workspace_bytes"):
+            fn = getattr(L, name)
+            fn.restype = sz
+            fn.argtypes = [i, i, i, i]
+        L.sage_quant_qk.restype = i
+        L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
+        L.sage_quant_v.restype = i
+        L.sage_quant_v.argtypes = [vp, vp, vp, f, i, i, i, i, i, vp, vp, sz]
+        L.sage_attn_fwd_quantized.restype = i
+        L.sage_attn_fwd_quantized.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, f, i, vp]
+        L.sage_attn_fwd.restype = i
+        L.sage_attn_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, vp, i, vp, sz]
+        _lib = L
+    return _lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise SageError(f"libsage error {code}: {lib().sage_strerror(code).decode()}")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return SAGE_F16
+    if t.dtype == torch.bfloat16:
+        return SAGE_BF16
+    raise SageError(f"unsupported dtype {t.dtype}: fp16 or bf16 expected")
+
+
+def _dev(*ts: torch.Tensor):
+    for t in ts:
+        if not t.is_cuda:
+            raise SageError("libsage needs device tensors (no CPU path exists)")
+        if not t.is_contiguous():
+            raise SageError("tensors must be contiguous [B, H, N, d]")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def get_params() -> dict:
+    p = _Params()
+    _check(lib().sage_get_params(ctypes.byref(p)))
+    return dict(bq=p.bq, bk=p.bk, w=p.w, v_tile=p.v_tile, p_r=p.p_r, v_r=p.v_r)
+
+
+def v_fp8_bytes(B, H, N, d) -> int:
+    return int(lib().sage_v_fp8_bytes(B, H, N, d))
+
+
+def quant_workspace_bytes(B, H, N, d) -> int:
+    return int(lib().sage_quant_workspace_bytes(B, H, N, d))
+
+
+def workspace_bytes(B, H, N, d) -> int:
+    return int(lib().sage_workspace_bytes(B, H, N, d))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def sage_quant_qk(q: torch.Tensor, k: torch.Tensor, workspace: torch.Tensor | None = None):
+    """-> (q_i8 [B,H,N,d], k_i8 [B,H,N,d], q_scale [B,H,nQ], k_scale [B,H,nK], k_mean [B,H,d])."""
+    _dev(q, k)
+    B, H, N, d = q.shape
+    if k.shape != q.shape or k.dtype != q.dtype:
+        raise SageError("q and k must have the same shape and dtype")
+    dev = q.device
+    nq, nk = -(-N // 128), -(-N // 64)
+    q_i8 = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    k_i8 = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    q_scale = torch.empty((B, H, nq), dtype=torch.float32, device=dev)
+    k_scale = torch.empty((B, H, nk), dtype=torch.float32, device=dev)
+    k_mean = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    need = quant_workspace_bytes(B, H, N, d)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    _check(lib().sage_quant_qk(q.data_ptr(), k.data_ptr(), q_i8.data_ptr(), k_i8.data_ptr(), q_scale.data_ptr(),
+                               k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d, _dt(q), _stream(),
+                               ws.data_ptr(), ws.numel()))
+    return q_i8, k_i8, q_scale, k_scale, k_mean
+
+
+def sage_quant_v(v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):
+    """-> (v_fp8 uint8 [B,H,ceil(N/128),d,128] in the library's tile layout, v_scale [B,H,d])."""
+    _dev(v)
+    B, H, N, d = v.shape
+    dev = v.device
+    nT = -(-N // 128)
+    v_fp8 = torch.empty((B, H, nT, d, 128), dtype=torch.uint8, device=dev)
+    v_scale = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    need = quant_workspace_bytes(B, H, N, d)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    _check(lib().sage_quant_v(v.data_ptr(), v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(v),
+                              _stream(), ws.data_ptr(), ws.numel()))
+    return v_fp8, v_scale
+
+
+def sage_attn_fwd_quantized(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, *, causal: bool, sm_scale: float,
+                            out_dtype: torch.dtype, p_r: float = 224.0, out: torch.Tensor | None = None):
+    _dev(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale)
+    B, H, N, d = q_i8.shape
+    if out is None:
+        out = torch.empty((B, H, N, d), dtype=out_dtype, device=q_i8.device)
+    _dev(out)
+    _check(lib().sage_attn_fwd_quantized(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
+                                         k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, H, N, d,
+                                         int(causal), float(sm_scale), float(p_r), _dt(out), _stream()))
+    return out
+
+
+def sage_attn_fwd(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None):
+    """Whole forward pass (quantisation + attention) with the default ranges."""
+    _dev(q, k, v)
+    B, H, N, d = q.shape
+    if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise SageError("q, k, v must have the same shape and dtype")
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    need = workspace_bytes(B, H, N, d)
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    _check(lib().sage_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d, int(causal),
+                               float(sm_scale), _stream(), _dt(q), ws.data_ptr(), ws.numel()))
+    return out
+
+
+def v_fp8_to_token_major(v_fp8: torch.Tensor, N: int) -> torch.Tensor:
+    """Undo the library's V tile layout: [B,H,T,d,128] -> codes [B,H,N,d] (layout bookkeeping only).
+
+    Byte 32*g + 4*t + i of a tile row is key 16*t + 4*g + i of that tile.
+    """
+    B, H, T, d, _ = v_fp8.shape
+    x = v_fp8.reshape(B, H, T, d, 4, 8, 4)          # [.., g, t, i]
+    x = x.permute(0, 1, 2, 5, 4, 6, 3)              # [B, H, T, t, g, i, d]
+    return x.reshape(B, H, T * 128, d)[:, :, :N].contiguous()

@@ -1,0 +1,38 @@
+// Internal launch interface between the C-ABI translation unit and the kernel
+// translation units of libsage (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sage {
+
+constexpr int kBQ = 128;        // tokens per Q quantisation block
+constexpr int kBK = 64;         // tokens per K quantisation block
+constexpr int kW = 128;         // keys per online-softmax step (= V tile)
+constexpr int kStatRows = 256;  // tokens per partial column statistic
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Scratch of the quantisation stage (all offsets 256-byte aligned).
+struct QuantScratch {
+    double *k_sum_part;  // [B*H][chunks][d]  partial column sums of K
+    float *v_max_part;   // [B*H][chunks][d]  partial column max|V|
+    float *v_rcp;        // [B*H][d]          V_r / max|V|
+    size_t bytes;
+};
+QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d);
+
+// stage 1 launches (sage_quant.hip)
+hipError_t launch_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
+                           float *k_scale, float *k_mean, int B, int H, int N, int d, bool bf16,
+                           hipStream_t stream, const QuantScratch &ws);
+hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
+                          int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
+
+// stage 2 launch (sage_attn.hip)
+hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+                       const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
+                       bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream);
+
+}  // namespace sage

@@ -1,0 +1,304 @@
+// Stage 1 of the SageAttention2++ 8+8 forward on gfx950: K smoothing, per-block
+// INT8 quantisation of Q and K, per-channel FP8 (E4M3) quantisation of V.
+//
+// All kernels here are bandwidth bound (read 2 bytes, write 1 byte per element
+// and tensor): every global access is a 16-byte load or a 8/16-byte store whose
+// lanes cover whole rows, statistics are reduced in registers -> LDS -> a small
+// partial buffer in a fixed order (no atomics), so results do not depend on
+// scheduling.
+//
+// This translation unit must be compiled with -ffp-contract=off: each quantiser
+// step (x - mean, a / range, range / a, x * r) is one correctly rounded binary32
+// operation, which is what makes codes and scales reproducible bit for bit
+// (paper Sec. 2.1 for the scales, Sec. 3 for the smoothing).
+#include "sage_internal.h"
+
+namespace sage {
+namespace {
+
+template <bool BF16>
+__device__ __forceinline__ float to_f32(uint32_t h16) {
+    if constexpr (BF16) {
+        return __builtin_bit_cast(float, h16 << 16);
+    } else {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void unpack8(const uint4 &u, float (&f)[8]) {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = to_f32<BF16>(w[i] & 0xffffu);
+        f[2 * i + 1] = to_f32<BF16>(w[i] >> 16);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Partial column statistics over chunks of kStatRows tokens.
+//   IS_V = false: sum_n K[n][c] in double (smoothing mean, Sec. 3)
+//   IS_V = true : max_n |V[n][c]|        (per-channel FP8 scale, Sec. 2.1)
+// grid (chunks, B*H), 256 threads; a thread owns 8 adjacent channels.
+// ---------------------------------------------------------------------------
+template <bool BF16, int D, bool IS_V>
+__global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restrict__ X, int N, int chunks,
+                                                       double *__restrict__ sum_part,
+                                                       float *__restrict__ max_part) {
+    constexpr int LPR = D / 8;     // lanes per row
+    constexpr int RP = 256 / LPR;  // rows per pass
+    using acc_t = typename std::conditional<IS_V, float, double>::type;
+    __shared__ acc_t sm[RP][D];
+
+    const int bh = blockIdx.y, chunk = blockIdx.x;
+    const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
+    const uint16_t *Xh = X + (size_t)bh * N * D;
+    const int r0 = chunk * kStatRows;
+    const int r1 = min(r0 + kStatRows, N);
+
+    acc_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0;
+    for (int r = r0 + rr; r < r1; r += RP) {
+        const uint4 u = *reinterpret_cast<const uint4 *>(Xh + (size_t)r * D + co * 8);
+        float f[8];
+        unpack8<BF16>(u, f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if constexpr (IS_V) {
+                acc[j] = fmaxf(acc[j], fabsf(f[j]));
+            } else {
+                acc[j] += (double)f[j];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[rr][co * 8 + j] = acc[j];
+    __syncthreads();
+    if (threadIdx.x < D) {
+        acc_t a = sm[0][threadIdx.x];
+        for (int i = 1; i < RP; ++i) {
+            if constexpr (IS_V) {
+                a = fmaxf(a, sm[i][threadIdx.x]);
+            } else {
+                a += sm[i][threadIdx.x];
+            }
+        }
+        const size_t o = ((size_t)bh * chunks + chunk) * D + threadIdx.x;
+        if constexpr (IS_V) {
+            max_part[o] = a;
+        } else {
+            sum_part[o] = a;
+        }
+    }
+}
+
+// mean[c] = float(sum / N): partial sums added in chunk order in double.
+__global__ void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N, int D,
+                                     float *__restrict__ mean) {
+    const int bh = blockIdx.x, c = threadIdx.x;
+    double s = 0.0;
+    for (int i = 0; i < chunks; ++i) s += sum_part[((size_t)bh * chunks + i) * D + c];
+    mean[(size_t)bh * D + c] = (float)(s / (double)N);
+}
+
+// delta_V[c] = a_c / V_r and the multiplier V_r / a_c (0 for an all-zero channel).
+__global__ void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D, float v_r,
+                                       float *__restrict__ v_scale, float *__restrict__ v_rcp) {
+    const int bh = blockIdx.x, c = threadIdx.x;
+    float a = 0.0f;
+    for (int i = 0; i < chunks; ++i) a = fmaxf(a, max_part[((size_t)bh * chunks + i) * D + c]);
+    v_scale[(size_t)bh * D + c] = a / v_r;
+    v_rcp[(size_t)bh * D + c] = a > 0.0f ? v_r / a : 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// Per-block INT8 quantisation (Sec. 2.1): one workgroup per block of BLOCK
+// tokens, the block lives in registers between the max pass and the code pass.
+// grid (blocks, B*H), 256 threads.
+// ---------------------------------------------------------------------------
+template <bool BF16, int D, int BLOCK, bool SMOOTH>
+__global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X,
+                                                         const float *__restrict__ mean,
+                                                         int8_t *__restrict__ codes,
+                                                         float *__restrict__ scale, int N, int nblk) {
+    constexpr int LPR = D / 8;
+    constexpr int RP = 256 / LPR;
+    constexpr int ITER = BLOCK / RP;
+    static_assert(BLOCK % RP == 0, "block must be a multiple of the rows covered per pass");
+    __shared__ float wmax[4];
+
+    const int bh = blockIdx.y, blk = blockIdx.x;
+    const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
+    const uint16_t *Xh = X + (size_t)bh * N * D;
+
+    float mu[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mu[j] = SMOOTH ? mean[(size_t)bh * D + co * 8 + j] : 0.0f;
+
+    float x[ITER][8];
+    float amax = 0.0f;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int r = blk * BLOCK + it * RP + rr;
+        if (r < N) {
+            const uint4 u = *reinterpret_cast<const uint4 *>(Xh + (size_t)r * D + co * 8);
+            unpack8<BF16>(u, x[it]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if constexpr (SMOOTH) x[it][j] = x[it][j] - mu[j];
+                amax = fmaxf(amax, fabsf(x[it][j]));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[it][j] = 0.0f;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    const float a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
+    if (threadIdx.x == 0) scale[(size_t)bh * nblk + blk] = a / 127.0f;
+
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int r = blk * BLOCK + it * RP + rr;
+        if (r < N) {
+            uint32_t w[2] = {0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = (int)__builtin_rintf(x[it][j] * rcp);
+                w[j >> 2] |= ((uint32_t)c & 0xffu) << (8 * (j & 3));
+            }
+            *reinterpret_cast<uint2 *>(codes + ((size_t)bh * N + r) * D + co * 8) = make_uint2(w[0], w[1]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-channel FP8 quantisation of V into the transposed, key-permuted tile
+// layout the attention kernel consumes: [B*H][tile][D][128] bytes, byte
+// 32*g + 4*t + i of a row = key 16*t + 4*g + i of the tile.  A thread converts
+// 4 consecutive keys x 8 channels, so the four keys of one channel pack into
+// one dword; the tile is transposed through LDS and leaves as one contiguous
+// D*128-byte burst.  grid (tiles, B*H), 256 threads.
+// ---------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict__ V,
+                                                      const float *__restrict__ v_rcp,
+                                                      uint8_t *__restrict__ Vt, int N, int nT) {
+    constexpr int LPR = D / 8;
+    constexpr int UPT = 32 * LPR / 256;  // (key quad, channel octet) units per thread
+    __shared__ uint32_t tile[D * 32];
+
+    const int bh = blockIdx.y, T = blockIdx.x;
+    const uint16_t *Vh = V + (size_t)bh * N * D;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+        const int u = threadIdx.x + 256 * k;
+        const int co = u % LPR, kq = u / LPR;
+        const int t = kq >> 2, g = kq & 3;
+        float rc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) rc[j] = v_rcp[(size_t)bh * D + co * 8 + j];
+        float y[4][8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = T * 128 + kq * 4 + i;
+            if (r < N) {
+                const uint4 raw = *reinterpret_cast<const uint4 *>(Vh + (size_t)r * D + co * 8);
+                unpack8<BF16>(raw, y[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) y[i][j] = y[i][j] * rc[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) y[i][j] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int w = 0;
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0][j], y[1][j], w, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2][j], y[3][j], w, true);
+            tile[(co * 8 + j) * 32 + g * 8 + t] = (uint32_t)w;
+        }
+    }
+    __syncthreads();
+    uint4 *dst = reinterpret_cast<uint4 *>(Vt + ((size_t)bh * nT + T) * D * 128);
+    const uint4 *src = reinterpret_cast<const uint4 *>(tile);
+#pragma unroll
+    for (int k = 0; k < D / 32; ++k) dst[threadIdx.x + 256 * k] = src[threadIdx.x + 256 * k];
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+template <bool BF16, int D>
+hipError_t quant_qk_impl(const uint16_t *q, const uint16_t *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
+                         float *k_scale, float *k_mean, int BH, int N, hipStream_t stream,
+                         const QuantScratch &ws) {
+    const int chunks = cdiv(N, kStatRows);
+    const int nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
+    colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, N, chunks, ws.k_sum_part, nullptr);
+    finalize_mean_kernel<<<BH, D, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
+    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
+    quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, k_mean, k_i8, k_scale, N, nK);
+    return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t quant_v_impl(const uint16_t *v, uint8_t *v_fp8, float *v_scale, float v_r, int BH, int N,
+                        hipStream_t stream, const QuantScratch &ws) {
+    const int chunks = cdiv(N, kStatRows);
+    const int nT = cdiv(N, kW);
+    colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, N, chunks, nullptr, ws.v_max_part);
+    finalize_vscale_kernel<<<BH, D, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
+    quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, ws.v_rcp, v_fp8, N, nT);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d) {
+    const size_t BH = (size_t)B * H;
+    const size_t chunks = (size_t)cdiv(N, kStatRows);
+    char *p = static_cast<char *>(base);
+    QuantScratch ws;
+    size_t off = 0;
+    ws.k_sum_part = reinterpret_cast<double *>(p + off);
+    off += align256(BH * chunks * d * sizeof(double));
+    ws.v_max_part = reinterpret_cast<float *>(p + off);
+    off += align256(BH * chunks * d * sizeof(float));
+    ws.v_rcp = reinterpret_cast<float *>(p + off);
+    off += align256(BH * d * sizeof(float));
+    ws.bytes = off;
+    return ws;
+}
+
+hipError_t launch_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
+                           float *k_scale, float *k_mean, int B, int H, int N, int d, bool bf16,
+                           hipStream_t stream, const QuantScratch &ws) {
+    const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k);
+    const int BH = B * H;
+    if (d == 128) {
+        return bf16 ? quant_qk_impl<true, 128>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws)
+                    : quant_qk_impl<false, 128>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws);
+    }
+    return bf16 ? quant_qk_impl<true, 64>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws)
+                : quant_qk_impl<false, 64>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws);
+}
+
+hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
+                          int d, bool bf16, hipStream_t stream, const QuantScratch &ws) {
+    const uint16_t *v16 = static_cast<const uint16_t *>(v);
+    const int BH = B * H;
+    if (d == 128) {
+        return bf16 ? quant_v_impl<true, 128>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws)
+                    : quant_v_impl<false, 128>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws);
+    }
+    return bf16 ? quant_v_impl<true, 64>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws)
+                : quant_v_impl<false, 64>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws);
+}
+
+}  // namespace sage

@@ -1,0 +1,93 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol the
+header declares; argument checks return error codes before any GPU call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_21136_amd as sage
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sage_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    names = _declared_functions()
+    assert sorted(sage.EXPORTS) == names
+    L = sage.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_params_and_sizes():
+    p = sage.get_params()
+    assert (p["bq"], p["bk"], p["w"], p["v_tile"]) == (128, 64, 128, 128)
+    assert p["p_r"] == 224.0 and p["v_r"] == 4.5          # paper Sec. 3.2
+    assert p["w"] % p["bk"] == 0 and p["bq"] % 16 == 0
+    assert sage.v_fp8_bytes(1, 48, 17776, 64) == 48 * 139 * 64 * 128
+    assert sage.v_fp8_bytes(1, 1, 1, 128) == 128 * 128
+    for shape in ((1, 2, 1024, 128), (1, 48, 17776, 64), (1, 1, 1, 64)):
+        qb, wb = sage.quant_workspace_bytes(*shape), sage.workspace_bytes(*shape)
+        B, H, N, d = shape
+        assert qb > 0 and qb % 256 == 0 and wb % 256 == 0
+        assert wb >= qb + 2 * B * H * N * d + sage.v_fp8_bytes(*shape)
+    # unsupported shapes report size 0
+    assert sage.workspace_bytes(1, 1, 16, 96) == 0 and sage.v_fp8_bytes(0, 1, 16, 64) == 0
+
+
+def test_argument_checks_return_codes_without_touching_the_gpu():
+    L = sage.lib()
+    buf = (ctypes.c_char * 4096)()
+    base = ctypes.addressof(buf)
+    p = (base + 255) & ~255      # 256-byte aligned host address: never dereferenced, checks fail first
+    EINVAL, EWS = -1, -2
+    # head dimension
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 96, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    # null pointer
+    assert L.sage_attn_fwd(None, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    # misaligned pointer
+    assert L.sage_attn_fwd(p + 2, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    # bad dtype, bad sizes
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 7, p, 1 << 20) == EINVAL
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 0, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    # workspace too small / missing
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, p, 16) == EWS
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, None, 1 << 20) == EWS
+    assert L.sage_quant_qk(p, p, p, p, p, p, p, 1, 1, 16, 64, 0, None, p, 0) == EWS
+    assert L.sage_quant_v(p, p, p, 4.5, 1, 1, 16, 64, 0, None, None, 0) == EWS
+    assert L.sage_quant_v(p, p, p, 0.0, 1, 1, 16, 64, 0, None, p, 1 << 20) == EINVAL
+    assert L.sage_quant_v(p, p, p, 500.0, 1, 1, 16, 64, 0, None, p, 1 << 20) == EINVAL
+    assert L.sage_attn_fwd_quantized(p, p, p, p, p, p, p, 1, 1, 16, 64, 0, 0.0, 1000.0, 0, None) == EINVAL
+    assert L.sage_attn_fwd_quantized(p, p, None, p, p, p, p, 1, 1, 16, 64, 0, 0.0, 224.0, 0, None) == EINVAL
+    for code in (0, -1, -2, -3, -99):
+        assert isinstance(L.sage_strerror(code), bytes) and len(L.sage_strerror(code)) > 0
+
+
+def test_no_cpu_fallback():
+    import torch
+    q = torch.zeros((1, 1, 16, 64), dtype=torch.float16)
+    with pytest.raises(sage.SageError):
+        sage.sage_attn_fwd(q, q, q, causal=False)
+
+
+def test_v_layout_helper_is_a_permutation():
+    import torch
+    T, d = 2, 64
+    # fill each byte with (key mod 251) by writing through the documented formula
+    buf = torch.zeros((1, 1, T, d, 128), dtype=torch.uint8)
+    for tile in range(T):
+        for g in range(4):
+            for t in range(8):
+                for i in range(4):
+                    key = tile * 128 + 16 * t + 4 * g + i
+                    buf[0, 0, tile, :, 32 * g + 4 * t + i] = key % 251
+    rows = sage.v_fp8_to_token_major(buf, 200)
+    assert rows.shape == (1, 1, 200, d)
+    want = (torch.arange(200) % 251).to(torch.uint8)[:, None].expand(200, d)
+    assert torch.equal(rows[0, 0], want)
