@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the SageAttention2++ 8+8 forward pass on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: K smoothing + INT8 quantisation of Q and K, FP8
+quantisation of V, fused attention -- the three C-ABI stage calls that
+``sage_attn_fwd`` makes, on one stream, with HIP events between them so that the
+attention kernel's own duration is measured inside the timed region.
+
+Prints ONE JSON line (metric: attention TOPS = 4*B*H*N^2*d / t, halved when
+causal), with the MFMA roofline of the attention kernel and the CPU oracle's
+throughput on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published dense peaks used for the roofline
+PEAK_MFMA_8BIT = 5.0e15      # INT8 and FP8 dense, op/s
+PEAK_HBM = 8.0e12            # B/s
+
+# HBM traffic of one attention-kernel launch measured with rocprofv3 --pmc
+# (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); filled from
+# the summaries under profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the d=128, N=32768 target workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path shards over batch*heads with no "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2505_21136_amd as sage
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    sage.lib()
+    cfg = {c.name: c for c in wl.CONFIGS}[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    q_h, k_h, v_h = wl.generate(cfg)
+    q, k, v = q_h.to(dev), k_h.to(dev), v_h.to(dev)
+    print(f"[bench] {cfg.name}: inputs generated and uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    B, H, N, d = cfg.B, cfg.H, cfg.N, cfg.d
+    sm_scale = float(np.float32(cfg.sm_scale))
+    out = torch.empty_like(q)
+    qws = torch.empty(sage.quant_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=dev)
+    # outputs of stage 1, allocated once (nothing is allocated inside the timed region)
+    q_i8, k_i8, q_scale, k_scale, k_mean = sage.sage_quant_qk(q, k, qws)
+    v_fp8, v_scale = sage.sage_quant_v(v, 4.5, qws)
+    L = sage.lib()
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    dt = 1 if cfg.dtype == "bf16" else 0
+
+    def step(ev=None):
+        rc = L.sage_quant_qk(q.data_ptr(), k.data_ptr(), q_i8.data_ptr(), k_i8.data_ptr(), q_scale.data_ptr(),
+                             k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d, dt, sp, qws.data_ptr(), qws.numel())
+        rc |= L.sage_quant_v(v.data_ptr(), v_fp8.data_ptr(), v_scale.data_ptr(), 4.5, B, H, N, d, dt, sp,
+                             qws.data_ptr(), qws.numel())
+        if ev:
+            ev[0].record(stream)
+        rc |= L.sage_attn_fwd_quantized(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
+                                        k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, H, N, d,
+                                        int(cfg.causal), sm_scale, 224.0, dt, sp)
+        if ev:
+            ev[1].record(stream)
+        if rc != 0:
+            raise RuntimeError("libsage call failed")
+
+    for _ in range(args.warmup):
+        step()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tops = cfg.ops / (elapsed / args.steps) / 1e12
+    attn_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+    attn_tops = cfg.ops / (attn_ms * 1e-3) / 1e12
+    quant_ms = ms_per_step - attn_ms
+    E = B * H * N * d
+    quant_gbs = 9.0 * E / (quant_ms * 1e-3) / 1e9 if quant_ms > 0 else None
+
+    result = {
+        "metric": "attention TOPS (4*B*H*N^2*d/s, halved when causal), quantisation + attention",
+        "value": round(tops, 2),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 (QK^T, int32 acc) + fp8 e4m3 (PV, fp32 acc); fp32 softmax",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={d} {'causal' if cfg.causal else 'non-causal'} "
+                               f"{cfg.dtype}, Q {cfg.q_dist}, K bias std 3"
+                               + (f", {cfg.k_outlier_channels} K outlier channels x20" if cfg.k_outlier_channels else ""),
+                   "p_r": 224.0, "v_r": 4.5, "bq": 128, "bk": 64, "w": 128},
+        "roofline": {
+            "kernel": "attn_kernel (fused INT8 QK^T + softmax + FP8 PV)",
+            "bound": "mfma",
+            "achieved": round(attn_tops, 2),
+            "peak": PEAK_MFMA_8BIT / 1e12,
+            "unit": "TFLOP/s",
+            "frac": round(attn_tops * 1e12 / PEAK_MFMA_8BIT, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "kernel_ms": round(attn_ms, 4),
+        },
+        "quant_stage": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_gbs, 1) if quant_gbs else None,
+                        "frac_of_hbm_peak": round(quant_gbs * 1e9 / PEAK_HBM, 4) if quant_gbs else None},
+    }
+
+    if not args.no_cpu_baseline:
+        result.update(cpu_baseline(cfg, q_h, k_h, v_h, out, args.cpu_seconds))
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, q_h, k_h, v_h, out, budget_s):
+    """Time the CPU oracle (as it stands) on a bounded sample: head (0,0), quantisation of the
+    whole head plus attention for evenly spaced query rows; compare the GPU output on those rows."""
+    import numpy as np
+
+    import oracle
+    import workloads as wl
+
+    qf, kf, vf = (wl.as_f32(t[0, 0]) for t in (q_h, k_h, v_h))
+    sm = np.float32(cfg.sm_scale)
+    N, d = cfg.N, cfg.d
+    t0 = time.perf_counter()
+    quant = oracle.quantize_head(qf, kf, vf)
+    t_quant = time.perf_counter() - t0
+
+    def rows_ops(r0, r1):
+        if cfg.causal:
+            return sum(4.0 * (r + 1) * d for r in range(r0, r1))
+        return 4.0 * (r1 - r0) * N * d
+
+    # pilot: one 16-row slab in the middle, then as many 128-row blocks as fit the budget
+    mid = (N // 2) // 128 * 128
+    t0 = time.perf_counter()
+    oracle.sage_attention_head(qf, kf, vf, causal=cfg.causal, sm_scale=sm, out_dtype=cfg.dtype,
+                               row0=mid, row1=min(N, mid + 16), quant=quant)
+    pilot = time.perf_counter() - t0
+    per_block = pilot * 8
+    nblk_total = -(-N // 128)
+    nblk = int(max(1, min(nblk_total, (budget_s - t_quant) / max(per_block, 1e-6))))
+    blocks = sorted({int(round(i * (nblk_total - 1) / max(nblk - 1, 1))) for i in range(nblk)})
+    ops = 0.0
+    refs, gots = [], []
+    t0 = time.perf_counter()
+    for i in blocks:
+        r0, r1 = i * 128, min(N, (i + 1) * 128)
+        ref, _ = oracle.sage_attention_head(qf, kf, vf, causal=cfg.causal, sm_scale=sm, out_dtype=cfg.dtype,
+                                            row0=r0, row1=r1, quant=quant)
+        ops += rows_ops(r0, r1)
+        refs.append(ref)
+        gots.append(out[0, 0, r0:r1].float().cpu().numpy())
+    t_attn = time.perf_counter() - t0
+    ref, got = np.concatenate(refs), np.concatenate(gots)
+    # the sample's share of the head's quantisation work is charged in proportion
+    share = sum(min(N, (i + 1) * 128) - i * 128 for i in blocks) / N
+    t_total = t_attn + t_quant * share
+    return {
+        "cpu_baseline": {"value": round(ops / t_total / 1e12, 6), "unit": "TOPS", "cores": oracle.num_threads(),
+                         "kind": "oracle",
+                         "sample": f"head (0,0): {len(blocks)} query blocks of 128 rows against all {N} keys "
+                                   f"({t_attn:.1f}s attention + {t_quant * share:.2f}s share of the head's quantisation)"},
+        "accuracy": {"rows": int(ref.shape[0]), "cos_vs_oracle": round(wl.cos_sim(ref, got), 7),
+                     "rel_l1_vs_oracle": float(f"{wl.rel_l1(ref, got):.3e}")},
+    }
+
+
+if __name__ == "__main__":
+    main()
