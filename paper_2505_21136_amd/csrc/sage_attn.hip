@@ -2,20 +2,25 @@
 // kernel (paper Sec. 2.1 for the tiling / online softmax and the scales,
 // Sec. 3.1 for the bounded FP8 range P_r of P~).
 //
-// Mapping to CDNA4.  A workgroup of 4 wavefronts owns BM = 64*NQ query rows of
-// one (batch, head); a wavefront owns NQ tiles of 16 query rows.  Per step of
-// 128 keys the K^ tile [128][D] int8 and the V^ tile [D][128] fp8 are staged in
-// LDS (16-byte chunks XOR-swizzled against bank conflicts).
+// Mapping to CDNA4.  A workgroup of NWAVE wavefronts owns BM = 16*NQ*NWAVE query
+// rows of one (batch, head); a wavefront owns NQ tiles of 16 query rows.  Per
+// step of 128 keys the K^ tile [128][D] int8 and the V^ tile [D][128] fp8 are
+// copied global -> LDS by buffer loads that write LDS directly (no register
+// staging, out-of-range rows read as zero), double buffered so that the copy of
+// step j+1 runs under the arithmetic of step j with one barrier per step.
+// 16-byte LDS chunks are XOR-swizzled against bank conflicts.
 //   S^T = K^ Q^T   with v_mfma_i32_16x16x64_i8 (keys are MFMA rows, queries are
 //                  MFMA columns).  A lane then holds, for ONE query (lane&15),
 //                  the scores of keys 16t + 4(lane>>4) + i, t<8, i<4: the row
 //                  maximum and sum are in-lane work plus two cross-lane steps.
 //   softmax        base 2, FP32; the de-quantisation constant
-//                  delta_Q*delta_K*sm_scale*log2(e) is one FMA operand, the
+//                  delta_Q*delta_K*sm_scale*log2(e) is one FMA operand (kept in
+//                  a VGPR: FMAs with a scalar operand issue at half rate), the
 //                  maximum is taken on the integer scores per 64-key K block.
 //   P^             v_cvt_pk_fp8_f32 in registers: the 32 bytes a lane produces
 //                  are exactly its B operand of v_mfma_f32_16x16x128_f8f6f4.
-//   O^T += V^T P^T with that instruction (FP8 E4M3 both sides, FP32 accumulate);
+//   O^T += V^T P^T with that instruction (FP8 E4M3 both sides, FP32 accumulate;
+//                  the older 16x16x32 fp8 MFMA runs at half its rate);
 //                  V^ is stored transposed and key-permuted by the quantiser so
 //                  that the A operand is 32 contiguous bytes of LDS.
 // The accumulator is rescaled only in steps where some row maximum moved
@@ -24,6 +29,7 @@
 
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 namespace sage {
 namespace {
@@ -31,20 +37,48 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
 
-// LDS byte offset of 16-byte chunk `c16` of row `row` of the K^ tile (row = key, D bytes per row).
+// 16-byte-chunk swizzles.  K^ tile: row = key, D bytes per row.  V^ tile: row = channel, 128 bytes per row.
+template <int D>
+__device__ __forceinline__ int k_swz(int row) {
+    return D == 128 ? (row & 7) : ((row >> 1) & 3);
+}
 template <int D>
 __device__ __forceinline__ int k_off(int row, int c16) {
-    if constexpr (D == 128) {
-        return row * 128 + ((c16 ^ (row & 7)) << 4);
-    } else {
-        return row * 64 + ((c16 ^ ((row >> 1) & 3)) << 4);
-    }
+    return row * D + ((c16 ^ k_swz<D>(row)) << 4);
 }
-// Same for the V^ tile (row = channel, 128 bytes = 8 chunks per row).
 __device__ __forceinline__ int v_off(int row, int c16) { return row * 128 + ((c16 ^ (row & 7)) << 4); }
 
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
+
+// Cross-lane exchange over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48).
+// v_permlane16_swap exchanges the odd rows of its first register with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second: starting from
+// two copies of x, the pair (a, b) then holds both partners' values in every lane.  The two copies
+// must live in distinct registers.
+// (Written as asm so that the two registers stay distinct; the s_nop around each swap cover the
+// wait states between vector ALU writes and a lane-permuting read/write of the same registers.)
+__device__ __forceinline__ void swap16(float &a, float &b) {
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap32(float &a, float &b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float rowgroup_max(float x) {
+    float a = x, b = x;
+    swap16(a, b);
+    a = b = fmaxf(a, b);
+    swap32(a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float rowgroup_sum(float x) {
+    float a = x, b = x;
+    swap16(a, b);
+    a = b = a + b;
+    swap32(a, b);
+    return a + b;
+}
 
 template <bool BF16>
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
@@ -60,19 +94,99 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     }
 }
 
-template <int D, int NQ, bool CAUSAL, bool BF16>
-__global__ __launch_bounds__(256, 2) void attn_kernel(
+// One online-softmax step for one 16-query tile: scores s[t] (t<8: 16-key tiles of the
+// 128-key step) -> P^ packed as the FP8 MFMA operand; updates m, l; returns alpha.
+// c0/c1: de-quantisation constants of the two 64-key K blocks of the step.
+// MASKED: keys beyond `lim` (causal diagonal or ragged tail) are excluded.
+template <bool MASKED>
+__device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, float log2_pr, float &m, float &l,
+                                              v8i &pb, int key_base, int lim) {
+    if constexpr (MASKED) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (key_base + 16 * t + i > lim) s[t][i] = INT_MIN;
+    }
+    // step maximum on the integers of each 64-key K block (its scale is positive)
+    int im0 = imax3(s[0][0], s[0][1], s[0][2]), im1 = imax3(s[4][0], s[4][1], s[4][2]);
+    im0 = max(im0, s[0][3]);
+    im1 = max(im1, s[4][3]);
+#pragma unroll
+    for (int t = 1; t < 4; ++t) {
+        im0 = imax3(im0, s[t][0], s[t][1]);
+        im0 = imax3(im0, s[t][2], s[t][3]);
+        im1 = imax3(im1, s[t + 4][0], s[t + 4][1]);
+        im1 = imax3(im1, s[t + 4][2], s[t + 4][3]);
+    }
+    float mc0 = (float)im0 * c0, mc1 = (float)im1 * c1;
+    if constexpr (MASKED) {
+        mc0 = im0 == INT_MIN ? -INFINITY : mc0;
+        mc1 = im1 == INT_MIN ? -INFINITY : mc1;
+    }
+    const float mc = rowgroup_max(fmaxf(mc0, mc1));
+    const float m_new = fmaxf(m, mc);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
+    float lsum0 = 0.0f, lsum1 = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const float cb = t < 4 ? c0 : c1;
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s[t][i], cb, mo));
+            if constexpr (MASKED) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
+        }
+        lsum0 += p[0] + p[1];
+        lsum1 += p[2] + p[3];
+        int w = 0;
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
+        pb[t] = w;
+    }
+    l = l * alpha + (lsum0 + lsum1);
+    m = m_new;
+    return alpha;
+}
+
+#if defined(__HIP_DEVICE_COMPILE__)
+// Enqueue the global -> LDS copy of the K^ and V^ tiles of key step j into one LDS stage.  Every
+// buffer load moves 16 bytes per lane straight into LDS at stage + 1024*(k*NWAVE + wave) + 16*lane;
+// the per-lane source offsets carry the swizzle, the tile offset rides in the scalar offset.
+template <int D, int NWAVE, int CPY>
+__device__ __forceinline__ void issue_copy(uint8_t *stage, __amdgpu_buffer_rsrc_t k_rsrc, __amdgpu_buffer_rsrc_t v_rsrc,
+                                           const int (&k_voff)[CPY], const int (&v_voff)[CPY], int wave, int j) {
+    constexpr int TILE = 128 * D;
+#pragma unroll
+    for (int k = 0; k < CPY; ++k) {
+        uint8_t *dstk = stage + (k * NWAVE + wave) * 1024;
+        uint8_t *dstv = dstk + TILE;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void *)dstk, 16, k_voff[k], j * TILE, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void *)dstv, 16, v_voff[k], j * TILE, 0, 0);
+    }
+}
+
+#endif  // __HIP_DEVICE_COMPILE__
+
+template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16>
+__global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const int8_t *__restrict__ Qc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
     uint16_t *__restrict__ out, int N, int nT, int nQblk, int nKblk, float sm_scale, float log2_pr) {
-    constexpr int BM = 64 * NQ;  // query rows per workgroup
-    constexpr int KC = D / 64;   // 64-wide contraction chunks of Q.K^T
-    constexpr int CT = D / 16;   // 16-channel tiles of the output
-    __shared__ __attribute__((aligned(16))) uint8_t Ks[128 * D];
-    __shared__ __attribute__((aligned(16))) uint8_t Vs[D * 128];
+#if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
+    constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
+    constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
+    constexpr int CT = D / 16;           // 16-channel tiles of the output
+    constexpr int TILE = 128 * D;        // bytes of one K^ (or V^) tile
+    constexpr int NTHR = NWAVE * 64;
+    constexpr int CPY = TILE / 16 / NTHR;  // 16-byte chunks each thread copies per tile
+    static_assert(TILE / 16 % NTHR == 0, "tile chunks must divide over the threads");
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[2][2 * TILE];  // [stage][K tile | V tile]
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
     // causal: heaviest (last) query tiles are launched first
@@ -83,6 +197,29 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int8_t *Qh = Qc + (size_t)bh * N * D;
     const int8_t *Kh = Kc + (size_t)bh * N * D;
     const uint8_t *Vh = Vt + (size_t)bh * nT * D * 128;
+    // buffer descriptors bounded to this head: rows >= N of K^ read as zero
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kh, 0, N * D, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vh, 0, nT * D * 128, 0x00020000);
+
+    // per-lane source offsets of the tile copies (the LDS side is linear in the lane index)
+    int k_voff[CPY], v_voff[CPY];
+#pragma unroll
+    for (int k = 0; k < CPY; ++k) {
+        const int slot = (k * NWAVE + wave) * 64 + lane;
+        {
+            constexpr int CPR = D / 16;  // chunks per K row
+            const int row = slot / CPR, pc = slot % CPR;
+            k_voff[k] = row * D + ((pc ^ k_swz<D>(row)) << 4);
+        }
+        {
+            const int row = slot >> 3, pc = slot & 7;
+            v_voff[k] = row * 128 + ((pc ^ (row & 7)) << 4);
+        }
+    }
+
+    int nsteps = nT;
+    if constexpr (CAUSAL) nsteps = min(N - 1, wg_row0 + BM - 1) / kW + 1;
+    issue_copy<D, NWAVE, CPY>(lds[0], k_rsrc, v_rsrc, k_voff, v_voff, wave, 0);
 
     v4i qreg[NQ][KC];
     double cq[NQ];
@@ -108,46 +245,32 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         for (int ct = 0; ct < CT; ++ct) o[ct][qt] = v4f{0.f, 0.f, 0.f, 0.f};
     }
 
-    int nsteps = nT;
-    if constexpr (CAUSAL) nsteps = min(N - 1, wg_row0 + BM - 1) / kW + 1;
-
     for (int j = 0; j < nsteps; ++j) {
         const int key0 = j * kW;
-        __syncthreads();  // every wave is done reading the previous tiles
-#pragma unroll
-        for (int k = 0; k < D / 32; ++k) {
-            const int e = tid + 256 * k;
-            const int row = e / (D / 16), c16 = e % (D / 16);
-            const int gr = key0 + row;
-            v4i val = {0, 0, 0, 0};
-            if (gr < N) val = *reinterpret_cast<const v4i *>(Kh + (size_t)gr * D + c16 * 16);
-            *reinterpret_cast<v4i *>(Ks + k_off<D>(row, c16)) = val;
-        }
-#pragma unroll
-        for (int k = 0; k < D / 32; ++k) {
-            const int e = tid + 256 * k;
-            const int row = e >> 3, c16 = e & 7;
-            const v4i val = *reinterpret_cast<const v4i *>(Vh + ((size_t)j * D + row) * 128 + c16 * 16);
-            *reinterpret_cast<v4i *>(Vs + v_off(row, c16)) = val;
-        }
+        const uint8_t *Ks = lds[j & 1];
+        const uint8_t *Vs = Ks + TILE;
+        // the copy of step j has landed (this wave's share), then everybody's: the barrier also
+        // guarantees that every wave is done reading the stage the next copy overwrites
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
         __syncthreads();
+        if (j + 1 < nsteps) issue_copy<D, NWAVE, CPY>(lds[(j + 1) & 1], k_rsrc, v_rsrc, k_voff, v_voff, wave, j + 1);
 
         // causal tile skipping at wavefront granularity: every key of this step lies
         // above every query row of this wavefront
         if (CAUSAL && key0 > row0 + 16 * NQ - 1) continue;
 
         // ---- S^T = K^ Q^T (INT8, INT32 accumulation) ----
-        v4i s[8][NQ];
+        v4i s[NQ][8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
 #pragma unroll
-            for (int qt = 0; qt < NQ; ++qt) s[t][qt] = v4i{0, 0, 0, 0};
+            for (int qt = 0; qt < NQ; ++qt) s[qt][t] = v4i{0, 0, 0, 0};
 #pragma unroll
             for (int ch = 0; ch < KC; ++ch) {
                 const v4i a = *reinterpret_cast<const v4i *>(Ks + k_off<D>(16 * t + lq, 4 * ch + g));
 #pragma unroll
                 for (int qt = 0; qt < NQ; ++qt)
-                    s[t][qt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], s[t][qt], 0, 0, 0);
+                    s[qt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], s[qt][t], 0, 0, 0);
             }
         }
 
@@ -159,55 +282,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         float alpha[NQ];
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
-            const float c0 = (float)(cq[qt] * dk0), c1 = (float)(cq[qt] * dk1);
+            float c0 = (float)(cq[qt] * dk0), c1 = (float)(cq[qt] * dk1);
+            asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
             if (masked_step) {
-                const int r = row0 + qt * 16 + lq;
-                int lim = N - 1;  // last visible key of this query row
-                if constexpr (CAUSAL) lim = min(lim, r);
-#pragma unroll
-                for (int t = 0; t < 8; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (key0 + 16 * t + 4 * g + i > lim) s[t][qt][i] = INT_MIN;
+                int lim = N - 1;  // last visible key of this lane's query row
+                if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq);
+                alpha[qt] = softmax_step<true>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim);
+            } else {
+                alpha[qt] = softmax_step<false>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], 0, 0);
             }
-            // step maximum, taken on the integers of each 64-key K block (its scale is positive)
-            int im0 = INT_MIN, im1 = INT_MIN;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                im0 = imax3(im0, s[t][qt][0], s[t][qt][1]);
-                im0 = imax3(im0, s[t][qt][2], s[t][qt][3]);
-                im1 = imax3(im1, s[t + 4][qt][0], s[t + 4][qt][1]);
-                im1 = imax3(im1, s[t + 4][qt][2], s[t + 4][qt][3]);
-            }
-            float mc0 = (float)im0 * c0, mc1 = (float)im1 * c1;
-            if (masked_step) {
-                mc0 = im0 == INT_MIN ? -INFINITY : mc0;
-                mc1 = im1 == INT_MIN ? -INFINITY : mc1;
-            }
-            float mc = fmaxf(mc0, mc1);
-            mc = fmaxf(mc, __shfl_xor(mc, 16));
-            mc = fmaxf(mc, __shfl_xor(mc, 32));
-            const float m_new = fmaxf(m[qt], mc);
-            alpha[qt] = __builtin_amdgcn_exp2f(m[qt] - m_new);
-            const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
-            float lsum = 0.0f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float cb = t < 4 ? c0 : c1;
-                float p[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s[t][qt][i], cb, mo));
-                    if (masked_step) p[i] = s[t][qt][i] == INT_MIN ? 0.0f : p[i];
-                }
-                lsum += (p[0] + p[1]) + (p[2] + p[3]);
-                int w = 0;
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
-                pb[qt][t] = w;
-            }
-            l[qt] = l[qt] * alpha[qt] + lsum;
-            m[qt] = m_new;
         }
 
         // ---- rescale O only when some running maximum moved ----
@@ -237,10 +320,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // ---- epilogue: O = acc * delta_V / (P_r * l); l already carries the factor P_r ----
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        float lt = l[qt];
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
-        const float inv = 1.0f / lt;
+        const float inv = 1.0f / rowgroup_sum(l[qt]);
         const int r = row0 + qt * 16 + lq;
         if (r < N) {
             uint16_t *orow = out + ((size_t)bh * N + r) * D;
@@ -254,19 +334,20 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
             }
         }
     }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int D, int NQ>
+template <int D, int NQ, int NWAVE, int WPS>
 hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                     const float *k_scale, const float *v_scale, void *out, int BH, int N, bool causal,
                     float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
-    constexpr int BM = 64 * NQ;
+    constexpr int BM = 16 * NQ * NWAVE;
     const dim3 grid(cdiv(N, BM), BH);
     const int nT = cdiv(N, kW), nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
-#define SAGE_LAUNCH(C, BF)                                                                             \
-    attn_kernel<D, NQ, C, BF><<<grid, 256, 0, stream>>>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, \
-                                                        o16, N, nT, nQ, nK, sm_scale, log2_pr)
+#define SAGE_LAUNCH(C, BF)                                                                                \
+    attn_kernel<D, NQ, NWAVE, WPS, C, BF><<<grid, NWAVE * 64, 0, stream>>>(q_i8, k_i8, v_fp8, q_scale, k_scale, \
+                                                                         v_scale, o16, N, nT, nQ, nK, sm_scale, log2_pr)
     if (causal) {
         if (bf16_out) SAGE_LAUNCH(true, true); else SAGE_LAUNCH(true, false);
     } else {
@@ -282,11 +363,24 @@ hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_
                        const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
                        bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
     const float log2_pr = (float)log2((double)p_r);
-    if (d == 128)
-        return launch_d<128, 2>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale,
-                                log2_pr, bf16_out, stream);
-    return launch_d<64, 2>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale,
-                           log2_pr, bf16_out, stream);
+    // experiment switch (tuning only): SAGE_ATTN_VARIANT=0..3
+    static const int variant = [] { const char *e = getenv("SAGE_ATTN_VARIANT"); return e ? atoi(e) : 0; }();
+#define SAGE_ARGS q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale, log2_pr, bf16_out, stream
+    if (d == 128) {
+        switch (variant) {
+            case 1: return launch_d<128, 2, 4, 2>(SAGE_ARGS);
+            case 2: return launch_d<128, 1, 4, 4>(SAGE_ARGS);
+            case 3: return launch_d<128, 2, 8, 2>(SAGE_ARGS);
+            default: return launch_d<128, 1, 8, 4>(SAGE_ARGS);
+        }
+    }
+    switch (variant) {
+        case 1: return launch_d<64, 2, 4, 2>(SAGE_ARGS);
+        case 2: return launch_d<64, 1, 4, 4>(SAGE_ARGS);
+        case 3: return launch_d<64, 2, 8, 2>(SAGE_ARGS);
+        default: return launch_d<64, 1, 8, 4>(SAGE_ARGS);
+    }
+#undef SAGE_ARGS
 }
 
 }  // namespace sage
