@@ -101,8 +101,8 @@ int sage_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8,
  * Layout of v_fp8 (private to this library but documented, because the codes
  * are part of the parity contract): [B*H][T = ceil(N/128)][d][128] bytes; the
  * 128 bytes of (tile T, channel c) hold the 128 keys of the tile permuted so
- * that byte 32*g + 4*t + i is key 128*T + 16*t + 4*g + i  (t<8, g<4, i<4);
- * keys >= N hold code 0.
+ * that byte 64*(t>>2) + 16*g + 4*(t&3) + i is key 128*T + 16*t + 4*g + i
+ * (t<8, g<4, i<4); keys >= N hold code 0.
  */
 int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r,
                  int B, int H, int N, int d, sage_dtype dt, void *stream,

@@ -184,9 +184,9 @@ def sage_attn_fwd(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torch.Te
 def v_fp8_to_token_major(v_fp8: torch.Tensor, N: int) -> torch.Tensor:
     """Undo the library's V tile layout: [B,H,T,d,128] -> codes [B,H,N,d] (layout bookkeeping only).
 
-    Byte 32*g + 4*t + i of a tile row is key 16*t + 4*g + i of that tile.
+    Byte 64*(t>>2) + 16*g + 4*(t&3) + i of a tile row is key 16*t + 4*g + i of that tile.
     """
     B, H, T, d, _ = v_fp8.shape
-    x = v_fp8.reshape(B, H, T, d, 4, 8, 4)          # [.., g, t, i]
-    x = x.permute(0, 1, 2, 5, 4, 6, 3)              # [B, H, T, t, g, i, d]
+    x = v_fp8.reshape(B, H, T, d, 2, 4, 4, 4)       # [.., t>>2, g, t&3, i]
+    x = x.permute(0, 1, 2, 4, 6, 5, 7, 3)           # [B, H, T, t>>2, t&3, g, i, d]
     return x.reshape(B, H, T * 128, d)[:, :, :N].contiguous()

@@ -16,13 +16,16 @@
 //   softmax        base 2, FP32; the de-quantisation constant
 //                  delta_Q*delta_K*sm_scale*log2(e) is one FMA operand (kept in
 //                  a VGPR: FMAs with a scalar operand issue at half rate), the
-//                  maximum is taken on the integer scores per 64-key K block.
+//                  maximum is taken on the integer scores per 64-key K block;
+//                  the INT32 accumulator starts at the bit pattern of 1.5*2^23,
+//                  which makes its bits a valid binary32 number (no conversion).
 //   P^             v_cvt_pk_fp8_f32 in registers: the 32 bytes a lane produces
 //                  are exactly its B operand of v_mfma_f32_16x16x128_f8f6f4.
 //   O^T += V^T P^T with that instruction (FP8 E4M3 both sides, FP32 accumulate;
 //                  the older 16x16x32 fp8 MFMA runs at half its rate);
 //                  V^ is stored transposed and key-permuted by the quantiser so
-//                  that the A operand is 32 contiguous bytes of LDS.
+//                  that the A operand is two 16-byte LDS chunks read in the same
+//                  conflict-free pattern as the K^ operand.
 // The accumulator is rescaled only in steps where some row maximum moved
 // (multiplying by alpha == 1 is the identity, so skipping is exact).
 #include "sage_internal.h"
@@ -94,13 +97,20 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     }
 }
 
-// One online-softmax step for one 16-query tile: scores s[t] (t<8: 16-key tiles of the
+// The INT8 MFMA accumulates onto kMagic = 0x4B400000 instead of 0: the INT32 result MAGIC + S,
+// read as binary32, IS the number K + S with K = 1.5*2^23 (exact for |S| < 2^22; |S| <= 127*127*128
+// here), so no int->float conversion instruction is needed.  -K*c is split exactly into two
+// binary32 numbers kh + kl; then fma(bits, c, kh) = fl(c*S - kl) and adding (kl + offset) restores c*S.
+constexpr int kMagic = 0x4B400000;
+constexpr float kMagicF = 12582912.0f;
+
+// One online-softmax step for one 16-query tile: biased scores s[t] (t<8: 16-key tiles of the
 // 128-key step) -> P^ packed as the FP8 MFMA operand; updates m, l; returns alpha.
-// c0/c1: de-quantisation constants of the two 64-key K blocks of the step.
+// c0/c1: de-quantisation constants of the two 64-key K blocks of the step; kh/kl: the exact split of -K*c.
 // MASKED: keys beyond `lim` (causal diagonal or ragged tail) are excluded.
 template <bool MASKED>
-__device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, float log2_pr, float &m, float &l,
-                                              v8i &pb, int key_base, int lim) {
+__device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, float kh0, float kh1, float kl0, float kl1, float log2_pr,
+                                              float &m, float &l, v8i &pb, int key_base, int lim) {
     if constexpr (MASKED) {
 #pragma unroll
         for (int t = 0; t < 8; ++t)
@@ -108,7 +118,7 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
             for (int i = 0; i < 4; ++i)
                 if (key_base + 16 * t + i > lim) s[t][i] = INT_MIN;
     }
-    // step maximum on the integers of each 64-key K block (its scale is positive)
+    // step maximum on the integers of each 64-key K block (its scale is positive; the bias keeps order)
     int im0 = imax3(s[0][0], s[0][1], s[0][2]), im1 = imax3(s[4][0], s[4][1], s[4][2]);
     im0 = max(im0, s[0][3]);
     im1 = max(im1, s[4][3]);
@@ -119,7 +129,8 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
         im1 = imax3(im1, s[t + 4][0], s[t + 4][1]);
         im1 = imax3(im1, s[t + 4][2], s[t + 4][3]);
     }
-    float mc0 = (float)im0 * c0, mc1 = (float)im1 * c1;
+    float mc0 = __builtin_fmaf(__builtin_bit_cast(float, im0), c0, kh0) + kl0;
+    float mc1 = __builtin_fmaf(__builtin_bit_cast(float, im1), c1, kh1) + kl1;
     if constexpr (MASKED) {
         mc0 = im0 == INT_MIN ? -INFINITY : mc0;
         mc1 = im1 == INT_MIN ? -INFINITY : mc1;
@@ -128,14 +139,16 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
     const float m_new = fmaxf(m, mc);
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
+    const float mo0 = mo + kl0, mo1 = mo + kl1;
     float lsum0 = 0.0f, lsum1 = 0.0f;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        const float cb = t < 4 ? c0 : c1;
+        const float cb = t < 4 ? c0 : c1, khb = t < 4 ? kh0 : kh1, mob = t < 4 ? mo0 : mo1;
         float p[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s[t][i], cb, mo));
+            const int sbits = s[t][i];  // (bit_cast needs a scalar object, not a vector element)
+            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(__builtin_bit_cast(float, sbits), cb, khb) + mob);
             if constexpr (MASKED) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
         }
         lsum0 += p[0] + p[1];
@@ -222,7 +235,6 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     issue_copy<D, NWAVE, CPY>(lds[0], k_rsrc, v_rsrc, k_voff, v_voff, wave, 0);
 
     v4i qreg[NQ][KC];
-    double cq[NQ];
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
         const int r = row0 + qt * 16 + lq;
@@ -231,9 +243,11 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             v4i z = {0, 0, 0, 0};
             qreg[qt][ch] = r < N ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
         }
-        const int blk = min(row0 + qt * 16, N - 1) / kBQ;
-        cq[qt] = (double)dq[(size_t)bh * nQblk + blk] * (double)sm_scale * 1.4426950408889634;
     }
+    // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
+    const double cq = (double)dq[(size_t)bh * nQblk + min(row0, N - 1) / kBQ] * (double)sm_scale * 1.4426950408889634;
+    float cvec = 0.0f;  // lane i: constant of K block 64*(j/32) + i, refreshed every 32 steps
+    const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
     float m[NQ], l[NQ];
     v4f o[CT][NQ];
@@ -259,37 +273,42 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         // above every query row of this wavefront
         if (CAUSAL && key0 > row0 + 16 * NQ - 1) continue;
 
-        // ---- S^T = K^ Q^T (INT8, INT32 accumulation) ----
+        // ---- S^T = K^ Q^T (INT8, INT32 accumulation onto the float-view bias) ----
+        // contraction chunk outermost: consecutive MFMAs never depend on each other
         v4i s[NQ][8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int ch = 0; ch < KC; ++ch) {
 #pragma unroll
-            for (int qt = 0; qt < NQ; ++qt) s[qt][t] = v4i{0, 0, 0, 0};
-#pragma unroll
-            for (int ch = 0; ch < KC; ++ch) {
+            for (int t = 0; t < 8; ++t) {
                 const v4i a = *reinterpret_cast<const v4i *>(Ks + k_off<D>(16 * t + lq, 4 * ch + g));
 #pragma unroll
                 for (int qt = 0; qt < NQ; ++qt)
-                    s[qt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], s[qt][t], 0, 0, 0);
+                    s[qt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], ch == 0 ? cinit : s[qt][t], 0, 0, 0);
             }
         }
 
-        const bool masked_step = (key0 + kW > N) || (CAUSAL && key0 + kW - 1 > row0);
-        const int kb0 = min(2 * j, nKblk - 1), kb1 = min(2 * j + 1, nKblk - 1);
-        const double dk0 = (double)dk[(size_t)bh * nKblk + kb0], dk1 = (double)dk[(size_t)bh * nKblk + kb1];
+        // de-quantisation constants of the two K blocks of this step
+        if ((j & 31) == 0) {
+            const int blk = min(64 * (j >> 5) + lane, nKblk - 1);
+            cvec = (float)(cq * (double)dk[(size_t)bh * nKblk + blk]);
+        }
+        float c0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j) & 63));
+        float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j + 1) & 63));
+        asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
+        const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;  // -K*c = kh + kl exactly
+        const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
 
+        const bool masked_step = (key0 + kW > N) || (CAUSAL && key0 + kW - 1 > row0);
         v8i pb[NQ];
         float alpha[NQ];
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
-            float c0 = (float)(cq[qt] * dk0), c1 = (float)(cq[qt] * dk1);
-            asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
             if (masked_step) {
                 int lim = N - 1;  // last visible key of this lane's query row
                 if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq);
-                alpha[qt] = softmax_step<true>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim);
+                alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim);
             } else {
-                alpha[qt] = softmax_step<false>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], 0, 0);
+                alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0);
             }
         }
 
@@ -308,8 +327,8 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             const int row = 16 * ct + lq;
-            const v4i lo = *reinterpret_cast<const v4i *>(Vs + v_off(row, 2 * g));
-            const v4i hi = *reinterpret_cast<const v4i *>(Vs + v_off(row, 2 * g + 1));
+            const v4i lo = *reinterpret_cast<const v4i *>(Vs + v_off(row, g));
+            const v4i hi = *reinterpret_cast<const v4i *>(Vs + v_off(row, 4 + g));
             const v8i a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
             for (int qt = 0; qt < NQ; ++qt)

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restr
 // ---------------------------------------------------------------------------
 // Per-channel FP8 quantisation of V into the transposed, key-permuted tile
 // layout the attention kernel consumes: [B*H][tile][D][128] bytes, byte
-// 32*g + 4*t + i of a row = key 16*t + 4*g + i of the tile.  A thread converts
+// 64*(t>>2) + 16*g + 4*(t&3) + i of a row = key 16*t + 4*g + i of the tile.  A thread converts
 // 4 consecutive keys x 8 channels, so the four keys of one channel pack into
 // one dword; the tile is transposed through LDS and leaves as one contiguous
 // D*128-byte burst.  grid (tiles, B*H), 256 threads.
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
             int w = 0;
             w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0][j], y[1][j], w, false);
             w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2][j], y[3][j], w, true);
-            tile[(co * 8 + j) * 32 + g * 8 + t] = (uint32_t)w;
+            tile[(co * 8 + j) * 32 + (t >> 2) * 16 + g * 4 + (t & 3)] = (uint32_t)w;
         }
     }
     __syncthreads();

@@ -86,7 +86,7 @@ def test_v_layout_helper_is_a_permutation():
             for t in range(8):
                 for i in range(4):
                     key = tile * 128 + 16 * t + 4 * g + i
-                    buf[0, 0, tile, :, 32 * g + 4 * t + i] = key % 251
+                    buf[0, 0, tile, :, 64 * (t >> 2) + 16 * g + 4 * (t & 3) + i] = key % 251
     rows = sage.v_fp8_to_token_major(buf, 200)
     assert rows.shape == (1, 1, 200, d)
     want = (torch.arange(200) % 251).to(torch.uint8)[:, None].expand(200, d)
