@@ -32,7 +32,6 @@
 
 #include <limits.h>
 #include <math.h>
-#include <stdlib.h>
 
 namespace sage {
 namespace {
@@ -164,24 +163,26 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
 }
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Enqueue the global -> LDS copy of the K^ and V^ tiles of key step j into one LDS stage.  Every
-// buffer load moves 16 bytes per lane straight into LDS at stage + 1024*(k*NWAVE + wave) + 16*lane;
-// the per-lane source offsets carry the swizzle, the tile offset rides in the scalar offset.
+// Enqueue the global -> LDS copy of one [128 x D]-byte tile (K^ or V^) of key step j.  Every buffer
+// load moves 16 bytes per lane straight into LDS at dst + 1024*(k*NWAVE + wave) + 16*lane; the
+// per-lane source offsets carry the swizzle, the tile offset rides in the scalar offset.
 template <int D, int NWAVE, int CPY>
-__device__ __forceinline__ void issue_copy(uint8_t *stage, __amdgpu_buffer_rsrc_t k_rsrc, __amdgpu_buffer_rsrc_t v_rsrc,
-                                           const int (&k_voff)[CPY], const int (&v_voff)[CPY], int wave, int j) {
+__device__ __forceinline__ void issue_tile_copy(uint8_t *dst, __amdgpu_buffer_rsrc_t rsrc, const int (&voff)[CPY],
+                                                int wave, int j) {
     constexpr int TILE = 128 * D;
 #pragma unroll
-    for (int k = 0; k < CPY; ++k) {
-        uint8_t *dstk = stage + (k * NWAVE + wave) * 1024;
-        uint8_t *dstv = dstk + TILE;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void *)dstk, 16, k_voff[k], j * TILE, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void *)dstv, 16, v_voff[k], j * TILE, 0, 0);
-    }
+    for (int k = 0; k < CPY; ++k)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + (k * NWAVE + wave) * 1024), 16, voff[k],
+                                                 j * TILE, 0, 0);
 }
-
 #endif  // __HIP_DEVICE_COMPILE__
 
+// Schedule.  The wavefronts of a workgroup form two groups (first and second half) that run the
+// same per-step sequence  M(j) = [PV(j-1), QK(j)]  ->  S(j) = softmax(j)  one slot apart: while
+// one group is in its matrix slot (MFMA + LDS reads) the other is in its softmax slot (vector
+// ALU), so the two pipes of every SIMD are busy at the same time instead of colliding.  A slot
+// ends with a workgroup barrier.  Tile copies for K^(j+1) and V^(j) are issued at the start of
+// slot 2j and are needed from slot 2j+2 on: two slots of latency to hide them.
 template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16>
 __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const int8_t *__restrict__ Qc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
@@ -195,11 +196,13 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     constexpr int NTHR = NWAVE * 64;
     constexpr int CPY = TILE / 16 / NTHR;  // 16-byte chunks each thread copies per tile
     static_assert(TILE / 16 % NTHR == 0, "tile chunks must divide over the threads");
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[2][2 * TILE];  // [stage][K tile | V tile]
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsK[2][TILE];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsV[2][TILE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >= NWAVE / 2 ? 1 : 0;  // second group runs one slot behind
     const int lq = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
     // causal: heaviest (last) query tiles are launched first
@@ -232,7 +235,10 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 
     int nsteps = nT;
     if constexpr (CAUSAL) nsteps = min(N - 1, wg_row0 + BM - 1) / kW + 1;
-    issue_copy<D, NWAVE, CPY>(lds[0], k_rsrc, v_rsrc, k_voff, v_voff, wave, 0);
+    // steps this wavefront takes part in (causal: tiles entirely above its rows are skipped)
+    int my_steps = nsteps;
+    if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1) / kW + 1);
+    issue_tile_copy<D, NWAVE, CPY>(ldsK[0], k_rsrc, k_voff, wave, 0);
 
     v4i qreg[NQ][KC];
 #pragma unroll
@@ -249,44 +255,76 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     float cvec = 0.0f;  // lane i: constant of K block 64*(j/32) + i, refreshed every 32 steps
     const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
-    float m[NQ], l[NQ];
+    float m[NQ], l[NQ], alpha[NQ];
     v4f o[CT][NQ];
+    v4i s[NQ][8];
+    v8i pb[NQ];
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
         m[qt] = -INFINITY;
         l[qt] = 0.0f;
+        alpha[qt] = 1.0f;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) o[ct][qt] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 8; ++t) s[qt][t] = cinit;
+        pb[qt] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
-    for (int j = 0; j < nsteps; ++j) {
-        const int key0 = j * kW;
-        const uint8_t *Ks = lds[j & 1];
-        const uint8_t *Vs = Ks + TILE;
-        // the copy of step j has landed (this wave's share), then everybody's: the barrier also
-        // guarantees that every wave is done reading the stage the next copy overwrites
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
-        __syncthreads();
-        if (j + 1 < nsteps) issue_copy<D, NWAVE, CPY>(lds[(j + 1) & 1], k_rsrc, v_rsrc, k_voff, v_voff, wave, j + 1);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): K^(0) has landed
+    __syncthreads();
 
-        // causal tile skipping at wavefront granularity: every key of this step lies
-        // above every query row of this wavefront
-        if (CAUSAL && key0 > row0 + 16 * NQ - 1) continue;
-
-        // ---- S^T = K^ Q^T (INT8, INT32 accumulation onto the float-view bias) ----
-        // contraction chunk outermost: consecutive MFMAs never depend on each other
-        v4i s[NQ][8];
+    // start of an even slot 2*jj: fetch K^(jj+1) and V^(jj)
+    auto issue_copies = [&](int jj) {
+        if (jj + 1 < nsteps) issue_tile_copy<D, NWAVE, CPY>(ldsK[(jj + 1) & 1], k_rsrc, k_voff, wave, jj + 1);
+        if (jj < nsteps) issue_tile_copy<D, NWAVE, CPY>(ldsV[jj & 1], v_rsrc, v_voff, wave, jj);
+    };
+    // matrix slot M(j): PV(j-1), then QK(j)
+    auto matrix_slot = [&](int j) {
+        if (j >= 1 && j <= my_steps) {
+            // ---- rescale O only when some running maximum moved ----
+            bool moved = false;
 #pragma unroll
-        for (int ch = 0; ch < KC; ++ch) {
+            for (int qt = 0; qt < NQ; ++qt) moved |= alpha[qt] != 1.0f;
+            if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const v4i a = *reinterpret_cast<const v4i *>(Ks + k_off<D>(16 * t + lq, 4 * ch + g));
+                for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                    for (int qt = 0; qt < NQ; ++qt) o[ct][qt] *= alpha[qt];
+            }
+            // ---- O^T += V^T P^T (FP8 E4M3 x E4M3, FP32 accumulation) ----
+            const uint8_t *Vs = ldsV[(j - 1) & 1];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const int row = 16 * ct + lq;
+                const v4i lo = *reinterpret_cast<const v4i *>(Vs + v_off(row, g));
+                const v4i hi = *reinterpret_cast<const v4i *>(Vs + v_off(row, 4 + g));
+                const v8i a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
                 for (int qt = 0; qt < NQ; ++qt)
-                    s[qt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], ch == 0 ? cinit : s[qt][t], 0, 0, 0);
+                    o[ct][qt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, pb[qt], o[ct][qt], 0, 0, 0, 0, 0, 0);
             }
         }
-
+        if (j < my_steps) {
+            // ---- S^T = K^ Q^T (INT8, INT32 accumulation onto the float-view bias) ----
+            // contraction chunk outermost: consecutive MFMAs never depend on each other
+            const uint8_t *Ks = ldsK[j & 1];
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const v4i a = *reinterpret_cast<const v4i *>(Ks + k_off<D>(16 * t + lq, 4 * ch + g));
+#pragma unroll
+                    for (int qt = 0; qt < NQ; ++qt)
+                        s[qt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, qreg[qt][ch], ch == 0 ? cinit : s[qt][t], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // softmax slot S(j)
+    auto softmax_slot = [&](int j) {
+        if (j >= my_steps) return;
+        const int key0 = j * kW;
         // de-quantisation constants of the two K blocks of this step
         if ((j & 31) == 0) {
             const int blk = min(64 * (j >> 5) + lane, nKblk - 1);
@@ -297,42 +335,43 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
         const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;  // -K*c = kh + kl exactly
         const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
-
         const bool masked_step = (key0 + kW > N) || (CAUSAL && key0 + kW - 1 > row0);
-        v8i pb[NQ];
-        float alpha[NQ];
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
             if (masked_step) {
                 int lim = N - 1;  // last visible key of this lane's query row
                 if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq);
-                alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim);
+                alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
+                                               key0 + 4 * g, lim);
             } else {
                 alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0);
             }
         }
+    };
 
-        // ---- rescale O only when some running maximum moved ----
-        bool moved = false;
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) moved |= alpha[qt] != 1.0f;
-        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int qt = 0; qt < NQ; ++qt) o[ct][qt] *= alpha[qt];
+    // 2*nsteps + 2 slots, one barrier each; copies issued at even slots are awaited at the end of
+    // the following odd slot
+    if (grp == 0) {
+        for (int j = 0; j <= nsteps; ++j) {
+            issue_copies(j);  // slot 2j
+            matrix_slot(j);
+            __syncthreads();
+            softmax_slot(j);  // slot 2j+1
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            __syncthreads();
         }
-
-        // ---- O^T += V^T P^T (FP8 E4M3 x E4M3, FP32 accumulation) ----
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const int row = 16 * ct + lq;
-            const v4i lo = *reinterpret_cast<const v4i *>(Vs + v_off(row, g));
-            const v4i hi = *reinterpret_cast<const v4i *>(Vs + v_off(row, 4 + g));
-            const v8i a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-#pragma unroll
-            for (int qt = 0; qt < NQ; ++qt)
-                o[ct][qt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, pb[qt], o[ct][qt], 0, 0, 0, 0, 0, 0);
+    } else {
+        issue_copies(0);  // slot 0: this group idles
+        __syncthreads();
+        for (int j = 0; j <= nsteps; ++j) {
+            matrix_slot(j);  // slot 2j+1
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            __syncthreads();
+            if (j < nsteps) {
+                issue_copies(j + 1);  // slot 2j+2
+                softmax_slot(j);
+                __syncthreads();
+            }
         }
     }
 
@@ -382,24 +421,14 @@ hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_
                        const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
                        bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
     const float log2_pr = (float)log2((double)p_r);
-    // experiment switch (tuning only): SAGE_ATTN_VARIANT=0..3
-    static const int variant = [] { const char *e = getenv("SAGE_ATTN_VARIANT"); return e ? atoi(e) : 0; }();
-#define SAGE_ARGS q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale, log2_pr, bf16_out, stream
-    if (d == 128) {
-        switch (variant) {
-            case 1: return launch_d<128, 2, 4, 2>(SAGE_ARGS);
-            case 2: return launch_d<128, 1, 4, 4>(SAGE_ARGS);
-            case 3: return launch_d<128, 2, 8, 2>(SAGE_ARGS);
-            default: return launch_d<128, 1, 8, 4>(SAGE_ARGS);
-        }
-    }
-    switch (variant) {
-        case 1: return launch_d<64, 2, 4, 2>(SAGE_ARGS);
-        case 2: return launch_d<64, 1, 4, 4>(SAGE_ARGS);
-        case 3: return launch_d<64, 2, 8, 2>(SAGE_ARGS);
-        default: return launch_d<64, 1, 8, 4>(SAGE_ARGS);
-    }
-#undef SAGE_ARGS
+    // 16 query rows per wavefront, 8 wavefronts (128 rows) per workgroup, 4 wavefronts per SIMD:
+    // the fastest of the measured shapes for both head dimensions (the kernel is bound by vector
+    // ALU issue, and more resident wavefronts overlap MFMA and VALU work better than wider tiles)
+    if (d == 128)
+        return launch_d<128, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale,
+                                      log2_pr, bf16_out, stream);
+    return launch_d<64, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale, log2_pr,
+                                 bf16_out, stream);
 }
 
 }  // namespace sage
