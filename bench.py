@@ -28,7 +28,10 @@ PEAK_HBM = 8.0e12            # B/s
 # HBM traffic of one attention-kernel launch measured with rocprofv3 --pmc
 # (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); filled from
 # the summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/attn_kernel_cfg5_counters.md: 836143 KiB x 2.0 fetched + 196608 KiB x 1.0 written
+    "cfg5": int(836143 * 1024 * 2.0 + 196608 * 1024 * 1.0),
+}
 
 
 def main():
@@ -39,6 +42,9 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the d=128, N=32768 target workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of Q (2E bytes read, 2E written) before the timed loop: "
+                         "the known-size kernel that FETCH_SIZE / WRITE_SIZE counter runs are scaled by")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -92,6 +98,10 @@ def main():
         if rc != 0:
             raise RuntimeError("libsage call failed")
 
+    if args.calib_copy:
+        calib = torch.empty_like(q)
+        calib.copy_(q)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
