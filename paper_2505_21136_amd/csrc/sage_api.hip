@@ -13,7 +13,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 bool shape_ok(int B, int H, int N, int d) {
-    return B >= 1 && H >= 1 && N >= 1 && (d == 64 || d == 128) && (size_t)B * H <= 65535u;
+    return B >= 1 && H >= 1 && N >= 1 && N <= (1 << 22) && (d == 64 || d == 128) && (size_t)B * H <= 65535u;
 }
 bool dtype_ok(sage_dtype dt) { return dt == SAGE_F16 || dt == SAGE_BF16; }
 int from_hip(hipError_t e) {

@@ -106,27 +106,39 @@ constexpr float kMagicF = 12582912.0f;
 // One online-softmax step for one 16-query tile: biased scores s[t] (t<8: 16-key tiles of the
 // 128-key step) -> P^ packed as the FP8 MFMA operand; updates m, l; returns alpha.
 // c0/c1: de-quantisation constants of the two 64-key K blocks of the step; kh/kl: the exact split of -K*c.
-// MASKED: keys beyond `lim` (causal diagonal or ragged tail) are excluded.
+// MASKED (causal diagonal or ragged tail): keys beyond `lim` are excluded.  The wavefront-uniform
+// bounds t_lo <= t_hi say which 16-key tiles need no mask (t < t_lo), an element-wise mask
+// (t_lo <= t < t_hi) or are invisible to every lane (t >= t_hi: no arithmetic at all, P^ = 0).
 template <bool MASKED>
 __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, float kh0, float kh1, float kl0, float kl1, float log2_pr,
-                                              float &m, float &l, v8i &pb, int key_base, int lim) {
+                                              float &m, float &l, v8i &pb, int key_base, int lim, int t_lo, int t_hi) {
+    // step maximum on the integers of each 64-key K block (its scale is positive; the bias keeps order)
+    int im0 = INT_MIN, im1 = INT_MIN;
     if constexpr (MASKED) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
+        for (int t = 0; t < 8; ++t) {
+            if (t >= t_hi) continue;
+            if (t >= t_lo) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (key_base + 16 * t + i > lim) s[t][i] = INT_MIN;
-    }
-    // step maximum on the integers of each 64-key K block (its scale is positive; the bias keeps order)
-    int im0 = imax3(s[0][0], s[0][1], s[0][2]), im1 = imax3(s[4][0], s[4][1], s[4][2]);
-    im0 = max(im0, s[0][3]);
-    im1 = max(im1, s[4][3]);
+                for (int i = 0; i < 4; ++i)
+                    if (key_base + 16 * t + i > lim) s[t][i] = INT_MIN;
+            }
+            int &im = t < 4 ? im0 : im1;
+            im = imax3(im, s[t][0], s[t][1]);
+            im = imax3(im, s[t][2], s[t][3]);
+        }
+    } else {
+        im0 = imax3(s[0][0], s[0][1], s[0][2]);
+        im1 = imax3(s[4][0], s[4][1], s[4][2]);
+        im0 = max(im0, s[0][3]);
+        im1 = max(im1, s[4][3]);
 #pragma unroll
-    for (int t = 1; t < 4; ++t) {
-        im0 = imax3(im0, s[t][0], s[t][1]);
-        im0 = imax3(im0, s[t][2], s[t][3]);
-        im1 = imax3(im1, s[t + 4][0], s[t + 4][1]);
-        im1 = imax3(im1, s[t + 4][2], s[t + 4][3]);
+        for (int t = 1; t < 4; ++t) {
+            im0 = imax3(im0, s[t][0], s[t][1]);
+            im0 = imax3(im0, s[t][2], s[t][3]);
+            im1 = imax3(im1, s[t + 4][0], s[t + 4][1]);
+            im1 = imax3(im1, s[t + 4][2], s[t + 4][3]);
+        }
     }
     float mc0 = __builtin_fmaf(__builtin_bit_cast(float, im0), c0, kh0) + kl0;
     float mc1 = __builtin_fmaf(__builtin_bit_cast(float, im1), c1, kh1) + kl1;
@@ -142,13 +154,24 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
     float lsum0 = 0.0f, lsum1 = 0.0f;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
+        if constexpr (MASKED) {
+            if (t >= t_hi) {
+                pb[t] = 0;
+                continue;
+            }
+        }
         const float cb = t < 4 ? c0 : c1, khb = t < 4 ? kh0 : kh1, mob = t < 4 ? mo0 : mo1;
         float p[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int sbits = s[t][i];  // (bit_cast needs a scalar object, not a vector element)
             p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(__builtin_bit_cast(float, sbits), cb, khb) + mob);
-            if constexpr (MASKED) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
+        }
+        if constexpr (MASKED) {
+            if (t >= t_lo) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
+            }
         }
         lsum0 += p[0] + p[1];
         lsum1 += p[2] + p[3];
@@ -204,9 +227,11 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = wave >= NWAVE / 2 ? 1 : 0;  // second group runs one slot behind
     const int lq = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.y;
-    // causal: heaviest (last) query tiles are launched first
-    const int qtile = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    // non-causal: grid (query tile, head) -- co-resident workgroups share a head's K^/V^ tiles in L2;
+    // causal: grid (head, query tile), longest rows first over ALL heads, so that the short
+    // workgroups fill the tail of the launch (greedy longest-first balances the CUs)
+    const int bh = CAUSAL ? (int)blockIdx.x : (int)blockIdx.y;
+    const int qtile = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.x;
     const int wg_row0 = qtile * BM;
     const int row0 = wg_row0 + wave * (16 * NQ);
 
@@ -341,10 +366,17 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             if (masked_step) {
                 int lim = N - 1;  // last visible key of this lane's query row
                 if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq);
+                // last visible key of the tile's first / last row: tiles wholly at or below the former
+                // need no mask, tiles wholly above the latter are invisible
+                const int lim_min = CAUSAL ? min(N - 1, row0 + qt * 16) : N - 1;
+                const int lim_max = CAUSAL ? min(N - 1, row0 + qt * 16 + 15) : N - 1;
+                const int t_lo = min(8, max(0, (lim_min - key0 + 1) >> 4));
+                const int t_hi = min(8, max(0, ((lim_max - key0) >> 4) + 1));
                 alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
-                                               key0 + 4 * g, lim);
+                                               key0 + 4 * g, lim, t_lo, t_hi);
             } else {
-                alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0);
+                alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0, 8,
+                                                8);
             }
         }
     };
@@ -400,7 +432,7 @@ hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8
                     const float *k_scale, const float *v_scale, void *out, int BH, int N, bool causal,
                     float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
     constexpr int BM = 16 * NQ * NWAVE;
-    const dim3 grid(cdiv(N, BM), BH);
+    const dim3 grid = causal ? dim3(BH, cdiv(N, BM)) : dim3(cdiv(N, BM), BH);
     const int nT = cdiv(N, kW), nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
 #define SAGE_LAUNCH(C, BF)                                                                                \

@@ -93,23 +93,38 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
     }
 }
 
-// mean[c] = float(sum / N): partial sums added in chunk order in double.
-__global__ void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N, int D,
-                                     float *__restrict__ mean) {
-    const int bh = blockIdx.x, c = threadIdx.x;
+// mean[c] = float(sum / N).  256 threads: 256/D threads share a channel, each adds every
+// (256/D)-th partial sum in chunk order, the shares are added in a fixed order through LDS
+// (the loads of one thread are independent, so the loop is not a chain of memory latencies).
+__global__ __launch_bounds__(256) void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N,
+                                                            int D, float *__restrict__ mean) {
+    __shared__ double sm[256];
+    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 256 / D;
     double s = 0.0;
-    for (int i = 0; i < chunks; ++i) s += sum_part[((size_t)bh * chunks + i) * D + c];
-    mean[(size_t)bh * D + c] = (float)(s / (double)N);
+    for (int i = part; i < chunks; i += parts) s += sum_part[((size_t)bh * chunks + i) * D + c];
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    if (part == 0) {
+        for (int k = 1; k < parts; ++k) s += sm[k * D + c];
+        mean[(size_t)bh * D + c] = (float)(s / (double)N);
+    }
 }
 
-// delta_V[c] = a_c / V_r and the multiplier V_r / a_c (0 for an all-zero channel).
-__global__ void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D, float v_r,
-                                       float *__restrict__ v_scale, float *__restrict__ v_rcp) {
-    const int bh = blockIdx.x, c = threadIdx.x;
+// delta_V[c] = a_c / V_r and the multiplier V_r / a_c (0 for an all-zero channel); same thread layout.
+__global__ __launch_bounds__(256) void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D,
+                                                              float v_r, float *__restrict__ v_scale,
+                                                              float *__restrict__ v_rcp) {
+    __shared__ float sm[256];
+    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 256 / D;
     float a = 0.0f;
-    for (int i = 0; i < chunks; ++i) a = fmaxf(a, max_part[((size_t)bh * chunks + i) * D + c]);
-    v_scale[(size_t)bh * D + c] = a / v_r;
-    v_rcp[(size_t)bh * D + c] = a > 0.0f ? v_r / a : 0.0f;
+    for (int i = part; i < chunks; i += parts) a = fmaxf(a, max_part[((size_t)bh * chunks + i) * D + c]);
+    sm[threadIdx.x] = a;
+    __syncthreads();
+    if (part == 0) {
+        for (int k = 1; k < parts; ++k) a = fmaxf(a, sm[k * D + c]);
+        v_scale[(size_t)bh * D + c] = a / v_r;
+        v_rcp[(size_t)bh * D + c] = a > 0.0f ? v_r / a : 0.0f;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -241,7 +256,7 @@ hipError_t quant_qk_impl(const uint16_t *q, const uint16_t *k, int8_t *q_i8, int
     const int chunks = cdiv(N, kStatRows);
     const int nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
     colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, N, chunks, ws.k_sum_part, nullptr);
-    finalize_mean_kernel<<<BH, D, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
+    finalize_mean_kernel<<<BH, 256, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
     quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
     quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, k_mean, k_i8, k_scale, N, nK);
     return hipGetLastError();
@@ -253,7 +268,7 @@ hipError_t quant_v_impl(const uint16_t *v, uint8_t *v_fp8, float *v_scale, float
     const int chunks = cdiv(N, kStatRows);
     const int nT = cdiv(N, kW);
     colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, N, chunks, nullptr, ws.v_max_part);
-    finalize_vscale_kernel<<<BH, D, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
+    finalize_vscale_kernel<<<BH, 256, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
     quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, ws.v_rcp, v_fp8, N, nT);
     return hipGetLastError();
 }
