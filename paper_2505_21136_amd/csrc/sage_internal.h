@@ -10,7 +10,7 @@ namespace sage {
 constexpr int kBQ = 128;        // tokens per Q quantisation block
 constexpr int kBK = 64;         // tokens per K quantisation block
 constexpr int kW = 128;         // keys per online-softmax step (= V tile)
-constexpr int kStatRows = 1024;  // tokens per partial column statistic
+constexpr int kStatRows = 256;   // tokens per partial column statistic
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 

@@ -93,13 +93,13 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
     }
 }
 
-// mean[c] = float(sum / N).  256 threads: 256/D threads share a channel, each adds every
-// (256/D)-th partial sum in chunk order, the shares are added in a fixed order through LDS
+// mean[c] = float(sum / N).  1024 threads: 1024/D threads share a channel, each adds every
+// (1024/D)-th partial sum in chunk order, the shares are added in a fixed order through LDS
 // (the loads of one thread are independent, so the loop is not a chain of memory latencies).
-__global__ __launch_bounds__(256) void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N,
-                                                            int D, float *__restrict__ mean) {
-    __shared__ double sm[256];
-    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 256 / D;
+__global__ __launch_bounds__(1024) void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N,
+                                                             int D, float *__restrict__ mean) {
+    __shared__ double sm[1024];
+    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
     double s = 0.0;
     for (int i = part; i < chunks; i += parts) s += sum_part[((size_t)bh * chunks + i) * D + c];
     sm[threadIdx.x] = s;
@@ -111,11 +111,11 @@ __global__ __launch_bounds__(256) void finalize_mean_kernel(const double *__rest
 }
 
 // delta_V[c] = a_c / V_r and the multiplier V_r / a_c (0 for an all-zero channel); same thread layout.
-__global__ __launch_bounds__(256) void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D,
-                                                              float v_r, float *__restrict__ v_scale,
-                                                              float *__restrict__ v_rcp) {
-    __shared__ float sm[256];
-    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 256 / D;
+__global__ __launch_bounds__(1024) void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D,
+                                                               float v_r, float *__restrict__ v_scale,
+                                                               float *__restrict__ v_rcp) {
+    __shared__ float sm[1024];
+    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
     float a = 0.0f;
     for (int i = part; i < chunks; i += parts) a = fmaxf(a, max_part[((size_t)bh * chunks + i) * D + c]);
     sm[threadIdx.x] = a;
@@ -256,9 +256,10 @@ hipError_t quant_qk_impl(const uint16_t *q, const uint16_t *k, int8_t *q_i8, int
     const int chunks = cdiv(N, kStatRows);
     const int nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
     colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, N, chunks, ws.k_sum_part, nullptr);
-    finalize_mean_kernel<<<BH, 256, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
-    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
+    finalize_mean_kernel<<<BH, 1024, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
+    // K right after its statistics pass: its second read can still be served by the last-level cache
     quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, k_mean, k_i8, k_scale, N, nK);
+    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
     return hipGetLastError();
 }
 
@@ -268,7 +269,7 @@ hipError_t quant_v_impl(const uint16_t *v, uint8_t *v_fp8, float *v_scale, float
     const int chunks = cdiv(N, kStatRows);
     const int nT = cdiv(N, kW);
     colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, N, chunks, nullptr, ws.v_max_part);
-    finalize_vscale_kernel<<<BH, 256, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
+    finalize_vscale_kernel<<<BH, 1024, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
     quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, ws.v_rcp, v_fp8, N, nT);
     return hipGetLastError();
 }

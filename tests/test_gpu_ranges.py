@@ -1,0 +1,49 @@
+"""A synthetic analogue of the paper's Table 2: attention accuracy against full precision for the
+feasible (P_r, V_r) pairs, measured through the GPU path.
+
+The paper reports that narrowing the FP8 ranges costs nothing (cosine 99.97 %, relative L1
+0.01862-0.01863 for all four rows, on CogVideoX activations).  Those activations are not
+available; the same comparison runs here on the seeded synthetic workloads.  Parity of every
+pair against the oracle is gated; the accuracy figures are printed and only their mutual
+agreement (the paper's qualitative claim) is checked."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_21136_amd as sage
+import workloads as wl
+from gpu_util import assert_parity, assert_quant_bit_exact, gpu_quant_all, oracle_quant_all, oracle_rows, say
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+PAIRS = [(448.0, 448.0), (448.0, 2.25), (224.0, 4.5), (112.0, 9.0)]   # rows of Table 2
+
+
+@pytest.mark.parametrize("idx", [1, 3, 5])
+def test_table2_analogue(idx):
+    cfg = wl.CONFIGS[idx - 1].scaled(B=1, H=2, N=2048)
+    q, k, v = wl.generate(cfg)
+    qf, kf, vf = (wl.as_f32(t) for t in (q, k, v))
+    sm = np.float32(cfg.sm_scale)
+    rows = slice(1024, 1280)
+    full = np.stack([oracle.attn_rows_fp(qf[0, h], kf[0, h], vf[0, h], causal=False, sm_scale=sm,
+                                         row0=rows.start, row1=rows.stop) for h in range(cfg.H)])
+    say(f"[table2] {cfg.name}-like, N={cfg.N} d={cfg.d} {cfg.dtype}: accuracy vs full precision")
+    l1s = []
+    for p_r, v_r in PAIRS:
+        got_q, dev = gpu_quant_all(q.to(DEV), k.to(DEV), v.to(DEV), v_r)
+        want_q = oracle_quant_all(qf, kf, vf, v_r)
+        assert_quant_bit_exact(got_q, want_q)
+        out = sage.sage_attn_fwd_quantized(dev["q_i8"], dev["k_i8"], dev["v_fp8"], dev["q_scale"], dev["k_scale"],
+                                           dev["v_scale"], causal=False, sm_scale=float(sm), out_dtype=q.dtype, p_r=p_r)
+        torch.cuda.synchronize()
+        got = out[0, :, rows].float().cpu().numpy()
+        ref = np.stack([oracle_rows(want_q, 0, h, rows.start, rows.stop, causal=False, sm_scale=sm,
+                                    out_dtype=cfg.dtype, p_r=p_r) for h in range(cfg.H)])
+        assert_parity(ref, got, f"P_r={p_r:g} V_r={v_r:g} vs oracle")
+        cos, l1, rm = wl.cos_sim(full, got), wl.rel_l1(full, got), wl.rmse(full, got)
+        say(f"   P_r={p_r:<5g} V_r={v_r:<5g} cos={100 * cos:.3f}%  relL1={l1:.5f}  rmse={rm:.3e}")
+        l1s.append(l1)
+    # the paper's claim: the choice among the feasible pairs barely matters
+    assert max(l1s) / min(l1s) < 1.05
