@@ -13,6 +13,7 @@ throughput on a bounded sample of the same workload.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -176,26 +177,26 @@ def cpu_baseline(cfg, q_h, k_h, v_h, out, budget_s):
             return sum(4.0 * (r + 1) * d for r in range(r0, r1))
         return 4.0 * (r1 - r0) * N * d
 
-    # pilot: one 16-row slab in the middle, then as many 128-row blocks as fit the budget
-    mid = (N // 2) // 128 * 128
-    t0 = time.perf_counter()
-    oracle.sage_attention_head(qf, kf, vf, causal=cfg.causal, sm_scale=sm, out_dtype=cfg.dtype,
-                               row0=mid, row1=min(N, mid + 16), quant=quant)
-    pilot = time.perf_counter() - t0
-    per_block = pilot * 8
+    # 128-row query blocks in a spread-out order (golden-ratio stride), until the time budget is used
     nblk_total = -(-N // 128)
-    nblk = int(max(1, min(nblk_total, (budget_s - t_quant) / max(per_block, 1e-6))))
-    blocks = sorted({int(round(i * (nblk_total - 1) / max(nblk - 1, 1))) for i in range(nblk)})
+    stride = max(1, int(nblk_total * 0.6180339887)) | 1
+    while math.gcd(stride, nblk_total) != 1:
+        stride += 2
+    order = [(i * stride) % nblk_total for i in range(nblk_total)]
+    blocks = []
     ops = 0.0
     refs, gots = [], []
     t0 = time.perf_counter()
-    for i in blocks:
+    for i in order:
         r0, r1 = i * 128, min(N, (i + 1) * 128)
         ref, _ = oracle.sage_attention_head(qf, kf, vf, causal=cfg.causal, sm_scale=sm, out_dtype=cfg.dtype,
                                             row0=r0, row1=r1, quant=quant)
         ops += rows_ops(r0, r1)
         refs.append(ref)
         gots.append(out[0, 0, r0:r1].float().cpu().numpy())
+        blocks.append(i)
+        if time.perf_counter() - t0 + t_quant > budget_s:
+            break
     t_attn = time.perf_counter() - t0
     ref, got = np.concatenate(refs), np.concatenate(gots)
     # the sample's share of the head's quantisation work is charged in proportion
