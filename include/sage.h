@@ -7,8 +7,10 @@
  * NULL = the default stream).  Inputs are never modified.
  *
  * Tensors.  Q, K, V and the output are contiguous [B, H, N, d] arrays of a
- * 16-bit floating type (`sage_dtype`), d in {64, 128}, N >= 1 arbitrary
- * (N_q = N_k = N, H_q = H_kv = H).
+ * 16-bit floating type (`sage_dtype`), d in {64, 128}, N >= 1 arbitrary.  The
+ * plain entry points take N_q = N_k = N and H_q = H_kv = H; the *_gqa entry
+ * points take Q/out as [B, Hq, Nq, d] and K/V as [B, Hkv, Nk, d], Hq a multiple
+ * of Hkv (query head h uses K/V head h / (Hq/Hkv)).
  *
  * The method (paper sections in brackets):
  *   stage 1  K is smoothed by subtracting its per-(b,h,channel) mean over the
@@ -71,6 +73,8 @@ size_t sage_v_fp8_bytes(int B, int H, int N, int d);
 size_t sage_quant_workspace_bytes(int B, int H, int N, int d);
 /* Scratch needed by sage_attn_fwd (quantised operands + scales + the above). */
 size_t sage_workspace_bytes(int B, int H, int N, int d);
+/* Same for sage_attn_fwd_gqa. */
+size_t sage_workspace_bytes_gqa(int B, int Hq, int Hkv, int Nq, int Nk, int d);
 
 /* ---- stage 1 ----------------------------------------------------------- */
 
@@ -90,6 +94,18 @@ int sage_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8,
                   float *q_scale, float *k_scale, float *k_mean,
                   int B, int H, int N, int d, sage_dtype dt, void *stream,
                   void *workspace, size_t workspace_bytes);
+
+/*
+ * The two halves of sage_quant_qk as separate calls, for inputs whose Q and K
+ * differ in head count or length (grouped-query attention, cross-attention,
+ * the models of Sec. 4.1 with fewer K/V heads than query heads).  Arguments,
+ * arithmetic and error behaviour as above; sage_quant_q needs no workspace.
+ */
+int sage_quant_q(const void *q, int8_t *q_i8, float *q_scale,
+                 int B, int H, int N, int d, sage_dtype dt, void *stream);
+int sage_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean,
+                 int B, int H, int N, int d, sage_dtype dt, void *stream,
+                 void *workspace, size_t workspace_bytes);
 
 /*
  * Per-channel FP8 E4M3 quantisation of V  [Sec. 2.1; Sec. 3.1 Eq. 2].
@@ -127,6 +143,20 @@ int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_
                             float p_r, sage_dtype out_dt, void *stream);
 
 /*
+ * Generalisation of sage_attn_fwd_quantized  [same passages]: Hq query heads over
+ * Hkv K/V heads (Hq % Hkv == 0), Nq query rows over Nk keys.
+ *   q_i8, q_scale, out   [B,Hq,Nq,d], [B,Hq,ceil(Nq/SAGE_BQ)], [B,Hq,Nq,d]
+ *   k_i8, k_scale        [B,Hkv,Nk,d], [B,Hkv,ceil(Nk/SAGE_BK)]
+ *   v_fp8, v_scale       sage_v_fp8_bytes(B,Hkv,Nk,d) bytes, [B,Hkv,d]
+ *   causal   the mask is aligned to the END of both sequences: key n is visible
+ *            to query r iff n <= r + (Nk - Nq); requires Nk >= Nq (SAGE_EINVAL otherwise)
+ */
+int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8,
+                                const float *q_scale, const float *k_scale, const float *v_scale,
+                                void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal,
+                                float sm_scale, float p_r, sage_dtype out_dt, void *stream);
+
+/*
  * The whole forward pass: sage_quant_qk + sage_quant_v + sage_attn_fwd_quantized
  * with the default ranges (P_r = 224, V_r = 4.5), intermediates in `workspace`
  * (device, >= sage_workspace_bytes(), 256-byte aligned).
@@ -136,6 +166,15 @@ int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_
 int sage_attn_fwd(const void *q, const void *k, const void *v, void *out,
                   int B, int H, int N, int d, int causal, float sm_scale, void *stream,
                   sage_dtype dt, void *workspace, size_t workspace_bytes);
+
+/*
+ * The whole forward pass for grouped-query / cross attention: sage_quant_k +
+ * sage_quant_v + sage_quant_q + sage_attn_fwd_quantized_gqa, default ranges,
+ * workspace >= sage_workspace_bytes_gqa().
+ */
+int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out,
+                      int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale,
+                      void *stream, sage_dtype dt, void *workspace, size_t workspace_bytes);
 
 #ifdef __cplusplus
 }

@@ -58,10 +58,10 @@ def _load():
         lib.sage_oracle_quant_v.restype = None
         lib.sage_oracle_quant_v.argtypes = [vp, c_i, c_i, c_f, vp, vp]
         lib.sage_oracle_attn_rows.restype = None
-        lib.sage_oracle_attn_rows.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_d, c_d,
+        lib.sage_oracle_attn_rows.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
                                               c_i, c_i, c_i, c_i, c_i, c_i, vp, vp]
         lib.sage_oracle_attn_rows_fp.restype = None
-        lib.sage_oracle_attn_rows_fp.argtypes = [vp, vp, vp, c_i, c_i, c_i, c_d, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_attn_rows_fp.argtypes = [vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_i, c_i, c_i, vp, vp]
         lib.sage_oracle_num_threads.restype = c_i
         lib.sage_oracle_num_threads.argtypes = []
         _lib = lib
@@ -154,19 +154,22 @@ def quant_v(V: np.ndarray, v_r: float = V_R):
 def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: float = P_R,
               bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
               out_dtype="bf16", want_p: bool = False):
+    """Quantised attention of query rows [row0, row1): Q^ is [Nq, d], K^ and V^ are [Nk, d]."""
     Qc, Kc = _c(Qc, np.int8), _c(Kc, np.int8)
     Vc = _c(Vc, np.uint8)
     dq, dk, dv = _c(dq, np.float32), _c(dk, np.float32), _c(dv, np.float32)
-    N, d = Qc.shape
-    assert Kc.shape == (N, d) and Vc.shape == (N, d) and dv.shape == (d,)
-    assert dq.shape == ((N + bq - 1) // bq,) and dk.shape == ((N + bk - 1) // bk,)
+    Nq, d = Qc.shape
+    Nk = Kc.shape[0]
+    assert Kc.shape == (Nk, d) and Vc.shape == (Nk, d) and dv.shape == (d,)
+    assert dq.shape == ((Nq + bq - 1) // bq,) and dk.shape == ((Nk + bk - 1) // bk,)
     assert w % bk == 0 or bk % w == 0
-    row1 = N if row1 is None else row1
-    assert 0 <= row0 <= row1 <= N
+    assert not causal or Nk >= Nq, "the end-aligned causal mask needs Nk >= Nq"
+    row1 = Nq if row1 is None else row1
+    assert 0 <= row0 <= row1 <= Nq
     code = {"fp16": 0, "bf16": 1, None: -1}[out_dtype]
     out = np.empty((row1 - row0, d), dtype=np.float64)
-    P = np.empty((row1 - row0, N), dtype=np.float64) if want_p else None
-    _load().sage_oracle_attn_rows(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), N, d, int(causal),
+    P = np.empty((row1 - row0, Nk), dtype=np.float64) if want_p else None
+    _load().sage_oracle_attn_rows(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
                                   float(sm_scale), float(p_r), bq, bk, w, row0, row1, code,
                                   _p(out), _p(P) if want_p else None)
     return (out, P) if want_p else out
@@ -174,13 +177,16 @@ def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: flo
 
 def attn_rows_fp(Q, K, V, *, causal: bool, sm_scale: float, w: int = W, row0: int = 0, row1=None,
                  want_p: bool = False):
-    """Block-wise online softmax on unquantised double operands (quantisers off)."""
+    """Block-wise online softmax on unquantised double operands (quantisers off); Q [Nq,d], K,V [Nk,d]."""
     Q, K, V = _c(Q, np.float64), _c(K, np.float64), _c(V, np.float64)
-    N, d = Q.shape
-    row1 = N if row1 is None else row1
+    Nq, d = Q.shape
+    Nk = K.shape[0]
+    assert K.shape == (Nk, d) and V.shape == (Nk, d)
+    assert not causal or Nk >= Nq
+    row1 = Nq if row1 is None else row1
     out = np.empty((row1 - row0, d), dtype=np.float64)
-    P = np.empty((row1 - row0, N), dtype=np.float64) if want_p else None
-    _load().sage_oracle_attn_rows_fp(_p(Q), _p(K), _p(V), N, d, int(causal), float(sm_scale), w,
+    P = np.empty((row1 - row0, Nk), dtype=np.float64) if want_p else None
+    _load().sage_oracle_attn_rows_fp(_p(Q), _p(K), _p(V), Nq, Nk, d, int(causal), float(sm_scale), w,
                                      row0, row1, _p(out), _p(P) if want_p else None)
     return (out, P) if want_p else out
 
@@ -208,11 +214,23 @@ def sage_attention_head(q, k, v, *, causal: bool, sm_scale: float, out_dtype: st
 
 
 def sage_attention(q, k, v, *, causal: bool, sm_scale: float, out_dtype: str, **kw):
-    """Whole path for a [B, H, N, d] problem (small sizes only)."""
-    B, H, N, d = q.shape
-    out = np.empty((B, H, N, d), dtype=np.float64)
+    """Whole path for q [B, Hq, Nq, d] and k, v [B, Hkv, Nk, d] (small sizes only).
+
+    Hq may be a multiple of Hkv (grouped-query attention: query head h uses K/V head h // (Hq/Hkv),
+    quantised once per K/V head); Nq may differ from Nk (causal: end-aligned)."""
+    B, Hq, Nq, d = q.shape
+    Hkv = k.shape[1]
+    assert Hq % Hkv == 0 and v.shape == k.shape
+    group = Hq // Hkv
+    out = np.empty((B, Hq, Nq, d), dtype=np.float64)
     for b in range(B):
-        for h in range(H):
-            out[b, h], _ = sage_attention_head(q[b, h], k[b, h], v[b, h], causal=causal,
-                                               sm_scale=sm_scale, out_dtype=out_dtype, **kw)
+        for hk in range(Hkv):
+            kv = dict(k_mean=k_mean(k[b, hk]))
+            kv["k_codes"], kv["k_scale"] = quant_int8(k[b, hk], kv["k_mean"], kw.get("bk", BK))
+            kv["v_codes"], kv["v_scale"] = quant_v(v[b, hk], kw.get("v_r", V_R))
+            for h in range(hk * group, (hk + 1) * group):
+                quant = dict(kv)
+                quant["q_codes"], quant["q_scale"] = quant_int8(q[b, h], None, kw.get("bq", BQ))
+                out[b, h], _ = sage_attention_head(q[b, h], k[b, hk], v[b, hk], causal=causal, sm_scale=sm_scale,
+                                                   out_dtype=out_dtype, quant=quant, **kw)
     return out

@@ -220,16 +220,26 @@ void sage_oracle_quant_v(const float *V, int N, int d, float v_r, uint8_t *codes
  *     acc   = alpha*acc + sum_n P^_n * V^[n][:]
  * and finally O[r][c] = acc[c] * delta_V[c] / (P_r * l), rounded to `out_dtype`
  * (0 fp16, 1 bf16, -1 no rounding).  For a causal row the loop stops after
- * the step that holds key r: later steps are fully masked and change nothing.
+ * the step that holds its last visible key: later steps are fully masked and
+ * change nothing.
+ *
+ * Q has Nq rows, K and V have Nk rows (Nq = Nk for self-attention).  With a
+ * causal mask and Nq != Nk the mask is aligned to the END of both sequences:
+ * key n is visible to query r iff n <= r + (Nk - Nq), which needs Nk >= Nq.
+ * Grouped-query attention is the caller's loop: several query heads use the
+ * same quantised K, V head.
  *
  * P_out, if not NULL, receives the normalised probabilities 2^(x - m_final)/l
- * as (row1-row0) x N doubles (test use only: rows must sum to one).          */
+ * as (row1-row0) x Nk doubles (test use only: rows must sum to one).         */
 void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc,
                            const float *dq, const float *dk, const float *dv,
-                           int N, int d, int causal, double sm_scale, double p_r,
+                           int Nq, int Nk, int d, int causal, double sm_scale, double p_r,
                            int BQ, int BK, int W, int row0, int row1, int out_dtype,
                            double *out, double *P_out)
 {
+    const int N = Nk;
+    const int shift = Nk - Nq; /* causal alignment */
+    (void)Nq;
     double *Vd = (double *)malloc((size_t)N * d * sizeof(double));
     for (size_t i = 0; i < (size_t)N * d; ++i)
         Vd[i] = sage_oracle_e4m3_decode(Vc[i]);
@@ -245,12 +255,12 @@ void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc
             double m = -INFINITY, l = 0.0;
             for (int c = 0; c < d; ++c)
                 acc[c] = 0.0;
-            int last = causal ? r : N - 1;
+            int last = causal ? r + shift : N - 1;
             for (int t0 = 0; t0 <= last; t0 += W) {
                 int t1 = t0 + W < N ? t0 + W : N;
                 double mx = -INFINITY;
                 for (int n = t0; n < t1; ++n) {
-                    if (causal && n > r) {
+                    if (causal && n > r + shift) {
                         x[n - t0] = -INFINITY;
                         continue;
                     }
@@ -304,9 +314,12 @@ void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc
  * that the tiling / online-softmax skeleton can be pinned against the plain
  * definition softmax(Q K^T * sm_scale) V.                                     */
 void sage_oracle_attn_rows_fp(const double *Q, const double *K, const double *V,
-                              int N, int d, int causal, double sm_scale, int W,
+                              int Nq, int Nk, int d, int causal, double sm_scale, int W,
                               int row0, int row1, double *out, double *P_out)
 {
+    const int N = Nk;
+    const int shift = Nk - Nq; /* causal alignment, as above */
+    (void)Nq;
 #pragma omp parallel
     {
         double *x = (double *)malloc((size_t)W * sizeof(double));
@@ -318,12 +331,12 @@ void sage_oracle_attn_rows_fp(const double *Q, const double *K, const double *V,
             double m = -INFINITY, l = 0.0;
             for (int c = 0; c < d; ++c)
                 acc[c] = 0.0;
-            int last = causal ? r : N - 1;
+            int last = causal ? r + shift : N - 1;
             for (int t0 = 0; t0 <= last; t0 += W) {
                 int t1 = t0 + W < N ? t0 + W : N;
                 double mx = -INFINITY;
                 for (int n = t0; n < t1; ++n) {
-                    if (causal && n > r) {
+                    if (causal && n > r + shift) {
                         x[n - t0] = -INFINITY;
                         continue;
                     }

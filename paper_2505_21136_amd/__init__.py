@@ -17,13 +17,16 @@ from . import build as _build
 
 __all__ = [
     "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
-    "sage_quant_qk", "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd", "v_fp8_to_token_major",
-    "EXPORTS",
+    "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
+    "sage_attn_fwd_quantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "workspace_bytes_gqa",
+    "v_fp8_to_token_major", "EXPORTS",
 ]
 
 SAGE_F16, SAGE_BF16 = 0, 1
 EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_workspace_bytes",
-           "sage_workspace_bytes", "sage_quant_qk", "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd"]
+           "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
+           "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa", "sage_attn_fwd",
+           "sage_attn_fwd_gqa"]
 
 
 class SageError(RuntimeError):
@@ -56,6 +59,16 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = sz
             fn.argtypes = [i, i, i, i]
+        L.sage_workspace_bytes_gqa.restype = sz
+        L.sage_workspace_bytes_gqa.argtypes = [i, i, i, i, i, i]
+        L.sage_quant_q.restype = i
+        L.sage_quant_q.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.sage_quant_k.restype = i
+        L.sage_quant_k.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
+        L.sage_attn_fwd_quantized_gqa.restype = i
+        L.sage_attn_fwd_quantized_gqa.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, vp]
+        L.sage_attn_fwd_gqa.restype = i
+        L.sage_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, i, vp, sz]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -111,6 +124,10 @@ def workspace_bytes(B, H, N, d) -> int:
     return int(lib().sage_workspace_bytes(B, H, N, d))
 
 
+def workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d) -> int:
+    return int(lib().sage_workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d))
+
+
 def _workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
@@ -134,6 +151,30 @@ def sage_quant_qk(q: torch.Tensor, k: torch.Tensor, workspace: torch.Tensor | No
                                k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d, _dt(q), _stream(),
                                ws.data_ptr(), ws.numel()))
     return q_i8, k_i8, q_scale, k_scale, k_mean
+
+
+def sage_quant_q(q: torch.Tensor):
+    """-> (q_i8 [B,H,N,d], q_scale [B,H,ceil(N/128)])."""
+    _dev(q)
+    B, H, N, d = q.shape
+    q_i8 = torch.empty((B, H, N, d), dtype=torch.int8, device=q.device)
+    q_scale = torch.empty((B, H, -(-N // 128)), dtype=torch.float32, device=q.device)
+    _check(lib().sage_quant_q(q.data_ptr(), q_i8.data_ptr(), q_scale.data_ptr(), B, H, N, d, _dt(q), _stream()))
+    return q_i8, q_scale
+
+
+def sage_quant_k(k: torch.Tensor, workspace: torch.Tensor | None = None):
+    """-> (k_i8 [B,H,N,d], k_scale [B,H,ceil(N/64)], k_mean [B,H,d])."""
+    _dev(k)
+    B, H, N, d = k.shape
+    dev = k.device
+    k_i8 = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    k_scale = torch.empty((B, H, -(-N // 64)), dtype=torch.float32, device=dev)
+    k_mean = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    ws = workspace if workspace is not None else _workspace(quant_workspace_bytes(B, H, N, d), dev)
+    _check(lib().sage_quant_k(k.data_ptr(), k_i8.data_ptr(), k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d,
+                              _dt(k), _stream(), ws.data_ptr(), ws.numel()))
+    return k_i8, k_scale, k_mean
 
 
 def sage_quant_v(v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):
@@ -161,6 +202,39 @@ def sage_attn_fwd_quantized(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, *, cau
     _check(lib().sage_attn_fwd_quantized(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
                                          k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, H, N, d,
                                          int(causal), float(sm_scale), float(p_r), _dt(out), _stream()))
+    return out
+
+
+def sage_attn_fwd_quantized_gqa(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, *, causal: bool, sm_scale: float,
+                                out_dtype: torch.dtype, p_r: float = 224.0, out: torch.Tensor | None = None):
+    """q_i8 [B,Hq,Nq,d] against k_i8 [B,Hkv,Nk,d] / v_fp8 of the same K/V shape."""
+    _dev(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale)
+    B, Hq, Nq, d = q_i8.shape
+    _, Hkv, Nk, _ = k_i8.shape
+    if out is None:
+        out = torch.empty((B, Hq, Nq, d), dtype=out_dtype, device=q_i8.device)
+    _dev(out)
+    _check(lib().sage_attn_fwd_quantized_gqa(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
+                                             k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq,
+                                             Nk, d, int(causal), float(sm_scale), float(p_r), _dt(out), _stream()))
+    return out
+
+
+def sage_attn_fwd_gqa(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torch.Tensor | None = None,
+                      workspace: torch.Tensor | None = None):
+    """Whole forward pass for q [B,Hq,Nq,d] and k, v [B,Hkv,Nk,d] (Hq % Hkv == 0)."""
+    _dev(q, k, v)
+    B, Hq, Nq, d = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[3] != d or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise SageError("k and v must share a shape [B,Hkv,Nk,d] and the dtype of q")
+    _, Hkv, Nk, _ = k.shape
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    need = workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d)
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    _check(lib().sage_attn_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d,
+                                   int(causal), float(sm_scale), _stream(), _dt(q), ws.data_ptr(), ws.numel()))
     return out
 
 

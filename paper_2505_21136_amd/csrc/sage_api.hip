@@ -1,5 +1,6 @@
 // C ABI of libsage (declared in include/sage.h): argument checks, workspace
-// carving and kernel launches.  No allocation, no synchronisation, no state.
+// carving and kernel launches.  No allocation, no synchronisation; the only
+// state is the last HIP error code of the calling thread (for sage_strerror).
 #include "../../include/sage.h"
 #include "sage_internal.h"
 
@@ -15,6 +16,9 @@ bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 bool shape_ok(int B, int H, int N, int d) {
     return B >= 1 && H >= 1 && N >= 1 && N <= (1 << 22) && (d == 64 || d == 128) && (size_t)B * H <= 65535u;
 }
+bool gqa_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal) {
+    return shape_ok(B, Hq, Nq, d) && shape_ok(B, Hkv, Nk, d) && Hq % Hkv == 0 && (!causal || Nk >= Nq);
+}
 bool dtype_ok(sage_dtype dt) { return dt == SAGE_F16 || dt == SAGE_BF16; }
 int from_hip(hipError_t e) {
     if (e == hipSuccess) return SAGE_OK;
@@ -28,29 +32,31 @@ struct FwdWorkspace {
     uint8_t *v_fp8;
     float *q_scale, *k_scale, *v_scale, *k_mean;
     void *quant;
+    size_t quant_bytes;
     size_t bytes;
 };
-FwdWorkspace fwd_layout(void *base, int B, int H, int N, int d) {
-    const size_t BH = (size_t)B * H, E = BH * N * d;
+FwdWorkspace fwd_layout(void *base, int B, int Hq, int Hkv, int Nq, int Nk, int d) {
+    const size_t Eq = (size_t)B * Hq * Nq * d, Ek = (size_t)B * Hkv * Nk * d, BHk = (size_t)B * Hkv;
     char *p = static_cast<char *>(base);
     size_t off = 0;
     FwdWorkspace w;
     w.q_i8 = reinterpret_cast<int8_t *>(p + off);
-    off += align256(E);
+    off += align256(Eq);
     w.k_i8 = reinterpret_cast<int8_t *>(p + off);
-    off += align256(E);
+    off += align256(Ek);
     w.v_fp8 = reinterpret_cast<uint8_t *>(p + off);
-    off += align256(sage_v_fp8_bytes(B, H, N, d));
+    off += align256(sage_v_fp8_bytes(B, Hkv, Nk, d));
     w.q_scale = reinterpret_cast<float *>(p + off);
-    off += align256(BH * sage::cdiv(N, sage::kBQ) * sizeof(float));
+    off += align256((size_t)B * Hq * sage::cdiv(Nq, sage::kBQ) * sizeof(float));
     w.k_scale = reinterpret_cast<float *>(p + off);
-    off += align256(BH * sage::cdiv(N, sage::kBK) * sizeof(float));
+    off += align256(BHk * sage::cdiv(Nk, sage::kBK) * sizeof(float));
     w.v_scale = reinterpret_cast<float *>(p + off);
-    off += align256(BH * d * sizeof(float));
+    off += align256(BHk * d * sizeof(float));
     w.k_mean = reinterpret_cast<float *>(p + off);
-    off += align256(BH * d * sizeof(float));
+    off += align256(BHk * d * sizeof(float));
     w.quant = p + off;
-    off += sage::quant_scratch_layout(nullptr, B, H, N, d).bytes;
+    w.quant_bytes = sage::quant_scratch_layout(nullptr, B, Hkv, Nk, d).bytes;
+    off += w.quant_bytes;
     w.bytes = off;
     return w;
 }
@@ -73,7 +79,9 @@ int sage_get_params(sage_params *out) {
 const char *sage_strerror(int code) {
     switch (code) {
         case SAGE_OK: return "success";
-        case SAGE_EINVAL: return "invalid argument (NULL or misaligned pointer, d not 64/128, size < 1, bad dtype or range)";
+        case SAGE_EINVAL:
+            return "invalid argument (NULL or misaligned pointer, d not 64/128, size out of range, bad dtype or FP8 "
+                   "range, Hq not a multiple of Hkv, causal with Nk < Nq)";
         case SAGE_EWORKSPACE: return "workspace missing, misaligned or too small";
         case SAGE_EHIP: return hipGetErrorString(g_last_hip_error);
         default: return "unknown error code";
@@ -90,22 +98,44 @@ size_t sage_quant_workspace_bytes(int B, int H, int N, int d) {
     return sage::quant_scratch_layout(nullptr, B, H, N, d).bytes;
 }
 
-size_t sage_workspace_bytes(int B, int H, int N, int d) {
-    if (!shape_ok(B, H, N, d)) return 0;
-    return fwd_layout(nullptr, B, H, N, d).bytes;
+size_t sage_workspace_bytes(int B, int H, int N, int d) { return sage_workspace_bytes_gqa(B, H, H, N, N, d); }
+
+size_t sage_workspace_bytes_gqa(int B, int Hq, int Hkv, int Nq, int Nk, int d) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, 0)) return 0;
+    return fwd_layout(nullptr, B, Hq, Hkv, Nq, Nk, d).bytes;
+}
+
+int sage_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int N, int d, sage_dtype dt,
+                 void *stream) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !q_i8 || !q_scale || !aligned16(q) || !aligned16(q_i8)) return SAGE_EINVAL;
+    return from_hip(sage::launch_quant_q(q, q_i8, q_scale, B, H, N, d, dt == SAGE_BF16,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+int sage_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H, int N, int d,
+                 sage_dtype dt, void *stream, void *workspace, size_t workspace_bytes) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!k || !k_i8 || !k_scale || !k_mean || !aligned16(k) || !aligned16(k_i8)) return SAGE_EINVAL;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
+        return SAGE_EWORKSPACE;
+    const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
+    return from_hip(sage::launch_quant_k(k, k_i8, k_scale, k_mean, B, H, N, d, dt == SAGE_BF16,
+                                         static_cast<hipStream_t>(stream), ws));
 }
 
 int sage_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale, float *k_scale,
                   float *k_mean, int B, int H, int N, int d, sage_dtype dt, void *stream, void *workspace,
                   size_t workspace_bytes) {
+    // every argument is checked before anything is enqueued
     if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
     if (!q || !k || !q_i8 || !k_i8 || !q_scale || !k_scale || !k_mean) return SAGE_EINVAL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(q_i8) || !aligned16(k_i8)) return SAGE_EINVAL;
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
         return SAGE_EWORKSPACE;
-    const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
-    return from_hip(sage::launch_quant_qk(q, k, q_i8, k_i8, q_scale, k_scale, k_mean, B, H, N, d,
-                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+    const int rc = sage_quant_k(k, k_i8, k_scale, k_mean, B, H, N, d, dt, stream, workspace, workspace_bytes);
+    if (rc != SAGE_OK) return rc;
+    return sage_quant_q(q, q_i8, q_scale, B, H, N, d, dt, stream);
 }
 
 int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
@@ -120,35 +150,50 @@ int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B
                                          static_cast<hipStream_t>(stream), ws));
 }
 
-int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                            const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
-                            int causal, float sm_scale, float p_r, sage_dtype out_dt, void *stream) {
-    if (!shape_ok(B, H, N, d) || !dtype_ok(out_dt)) return SAGE_EINVAL;
+int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+                                const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv,
+                                int Nq, int Nk, int d, int causal, float sm_scale, float p_r, sage_dtype out_dt,
+                                void *stream) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(out_dt)) return SAGE_EINVAL;
     if (!q_i8 || !k_i8 || !v_fp8 || !q_scale || !k_scale || !v_scale || !out) return SAGE_EINVAL;
     if (!aligned16(q_i8) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
     if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
-    return from_hip(sage::launch_attn(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, H, N, d, causal != 0,
-                                      sm_scale, p_r, out_dt == SAGE_BF16, static_cast<hipStream_t>(stream)));
+    return from_hip(sage::launch_attn(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
+                                      causal != 0, sm_scale, p_r, out_dt == SAGE_BF16,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+                            const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
+                            int causal, float sm_scale, float p_r, sage_dtype out_dt, void *stream) {
+    return sage_attn_fwd_quantized_gqa(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, H, H, N, N, d, causal,
+                                       sm_scale, p_r, out_dt, stream);
+}
+
+int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                      int d, int causal, float sm_scale, void *stream, sage_dtype dt, void *workspace,
+                      size_t workspace_bytes) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !k || !v || !out) return SAGE_EINVAL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return SAGE_EINVAL;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d))
+        return SAGE_EWORKSPACE;
+    const FwdWorkspace w = fwd_layout(workspace, B, Hq, Hkv, Nq, Nk, d);
+    int rc = sage_quant_k(k, w.k_i8, w.k_scale, w.k_mean, B, Hkv, Nk, d, dt, stream, w.quant, w.quant_bytes);
+    if (rc != SAGE_OK) return rc;
+    rc = sage_quant_v(v, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk, d, dt, stream, w.quant, w.quant_bytes);
+    if (rc != SAGE_OK) return rc;
+    rc = sage_quant_q(q, w.q_i8, w.q_scale, B, Hq, Nq, d, dt, stream);
+    if (rc != SAGE_OK) return rc;
+    return sage_attn_fwd_quantized_gqa(w.q_i8, w.k_i8, w.v_fp8, w.q_scale, w.k_scale, w.v_scale, out, B, Hq, Hkv, Nq,
+                                       Nk, d, causal, sm_scale, 224.0f, dt, stream);
 }
 
 int sage_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H, int N, int d, int causal,
                   float sm_scale, void *stream, sage_dtype dt, void *workspace, size_t workspace_bytes) {
-    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
-    if (!q || !k || !v || !out) return SAGE_EINVAL;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return SAGE_EINVAL;
-    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_workspace_bytes(B, H, N, d))
-        return SAGE_EWORKSPACE;
-    const FwdWorkspace w = fwd_layout(workspace, B, H, N, d);
-    const size_t qbytes = sage_quant_workspace_bytes(B, H, N, d);
-    int rc = sage_quant_qk(q, k, w.q_i8, w.k_i8, w.q_scale, w.k_scale, w.k_mean, B, H, N, d, dt, stream, w.quant,
-                           qbytes);
-    if (rc != SAGE_OK) return rc;
-    rc = sage_quant_v(v, w.v_fp8, w.v_scale, 4.5f, B, H, N, d, dt, stream, w.quant, qbytes);
-    if (rc != SAGE_OK) return rc;
-    return sage_attn_fwd_quantized(w.q_i8, w.k_i8, w.v_fp8, w.q_scale, w.k_scale, w.v_scale, out, B, H, N, d,
-                                   causal, sm_scale, 224.0f, dt, stream);
+    return sage_attn_fwd_gqa(q, k, v, out, B, H, H, N, N, d, causal, sm_scale, stream, dt, workspace, workspace_bytes);
 }
 
 }  // extern "C"

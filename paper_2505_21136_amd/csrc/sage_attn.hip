@@ -210,7 +210,8 @@ template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16>
 __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const int8_t *__restrict__ Qc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
-    uint16_t *__restrict__ out, int N, int nT, int nQblk, int nKblk, float sm_scale, float log2_pr) {
+    uint16_t *__restrict__ out, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq, int group, float sm_scale,
+    float log2_pr) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
     constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
     constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
@@ -230,16 +231,20 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // non-causal: grid (query tile, head) -- co-resident workgroups share a head's K^/V^ tiles in L2;
     // causal: grid (head, query tile), longest rows first over ALL heads, so that the short
     // workgroups fill the tail of the launch (greedy longest-first balances the CUs)
-    const int bh = CAUSAL ? (int)blockIdx.x : (int)blockIdx.y;
+    const int bh = CAUSAL ? (int)blockIdx.x : (int)blockIdx.y;  // (batch, query head)
     const int qtile = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.x;
     const int wg_row0 = qtile * BM;
     const int row0 = wg_row0 + wave * (16 * NQ);
+    // grouped-query attention: `group` consecutive query heads share one K/V head
+    const int bhk = (bh / Hq) * (Hq / group) + (bh % Hq) / group;
+    // causal mask aligned to the end of both sequences: key n visible to query r iff n <= r + shift
+    const int shift = Nk - Nq;
 
-    const int8_t *Qh = Qc + (size_t)bh * N * D;
-    const int8_t *Kh = Kc + (size_t)bh * N * D;
-    const uint8_t *Vh = Vt + (size_t)bh * nT * D * 128;
-    // buffer descriptors bounded to this head: rows >= N of K^ read as zero
-    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kh, 0, N * D, 0x00020000);
+    const int8_t *Qh = Qc + (size_t)bh * Nq * D;
+    const int8_t *Kh = Kc + (size_t)bhk * Nk * D;
+    const uint8_t *Vh = Vt + (size_t)bhk * nT * D * 128;
+    // buffer descriptors bounded to this head: rows >= Nk of K^ read as zero
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kh, 0, Nk * D, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vh, 0, nT * D * 128, 0x00020000);
 
     // per-lane source offsets of the tile copies (the LDS side is linear in the lane index)
@@ -259,10 +264,10 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     }
 
     int nsteps = nT;
-    if constexpr (CAUSAL) nsteps = min(N - 1, wg_row0 + BM - 1) / kW + 1;
+    if constexpr (CAUSAL) nsteps = min(Nk - 1, wg_row0 + BM - 1 + shift) / kW + 1;
     // steps this wavefront takes part in (causal: tiles entirely above its rows are skipped)
     int my_steps = nsteps;
-    if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1) / kW + 1);
+    if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
     issue_tile_copy<D, NWAVE, CPY>(ldsK[0], k_rsrc, k_voff, wave, 0);
 
     v4i qreg[NQ][KC];
@@ -272,11 +277,11 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 #pragma unroll
         for (int ch = 0; ch < KC; ++ch) {
             v4i z = {0, 0, 0, 0};
-            qreg[qt][ch] = r < N ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
+            qreg[qt][ch] = r < Nq ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
         }
     }
     // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
-    const double cq = (double)dq[(size_t)bh * nQblk + min(row0, N - 1) / kBQ] * (double)sm_scale * 1.4426950408889634;
+    const double cq = (double)dq[(size_t)bh * nQblk + min(row0, Nq - 1) / kBQ] * (double)sm_scale * 1.4426950408889634;
     float cvec = 0.0f;  // lane i: constant of K block 64*(j/32) + i, refreshed every 32 steps
     const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
@@ -353,23 +358,23 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         // de-quantisation constants of the two K blocks of this step
         if ((j & 31) == 0) {
             const int blk = min(64 * (j >> 5) + lane, nKblk - 1);
-            cvec = (float)(cq * (double)dk[(size_t)bh * nKblk + blk]);
+            cvec = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk]);
         }
         float c0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j) & 63));
         float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j + 1) & 63));
         asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
         const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;  // -K*c = kh + kl exactly
         const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
-        const bool masked_step = (key0 + kW > N) || (CAUSAL && key0 + kW - 1 > row0);
+        const bool masked_step = (key0 + kW > Nk) || (CAUSAL && key0 + kW - 1 > row0 + shift);
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
             if (masked_step) {
-                int lim = N - 1;  // last visible key of this lane's query row
-                if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq);
+                int lim = Nk - 1;  // last visible key of this lane's query row
+                if constexpr (CAUSAL) lim = min(lim, row0 + qt * 16 + lq + shift);
                 // last visible key of the tile's first / last row: tiles wholly at or below the former
                 // need no mask, tiles wholly above the latter are invisible
-                const int lim_min = CAUSAL ? min(N - 1, row0 + qt * 16) : N - 1;
-                const int lim_max = CAUSAL ? min(N - 1, row0 + qt * 16 + 15) : N - 1;
+                const int lim_min = CAUSAL ? min(Nk - 1, row0 + qt * 16 + shift) : Nk - 1;
+                const int lim_max = CAUSAL ? min(Nk - 1, row0 + qt * 16 + 15 + shift) : Nk - 1;
                 const int t_lo = min(8, max(0, (lim_min - key0 + 1) >> 4));
                 const int t_hi = min(8, max(0, ((lim_max - key0) >> 4) + 1));
                 alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
@@ -412,12 +417,12 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     for (int qt = 0; qt < NQ; ++qt) {
         const float inv = 1.0f / rowgroup_sum(l[qt]);
         const int r = row0 + qt * 16 + lq;
-        if (r < N) {
-            uint16_t *orow = out + ((size_t)bh * N + r) * D;
+        if (r < Nq) {
+            uint16_t *orow = out + ((size_t)bh * Nq + r) * D;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 const int c = 16 * ct + 4 * g;
-                const float4 sc = *reinterpret_cast<const float4 *>(dv + (size_t)bh * D + c);
+                const float4 sc = *reinterpret_cast<const float4 *>(dv + (size_t)bhk * D + c);
                 const float y0 = o[ct][qt][0] * (sc.x * inv), y1 = o[ct][qt][1] * (sc.y * inv);
                 const float y2 = o[ct][qt][2] * (sc.z * inv), y3 = o[ct][qt][3] * (sc.w * inv);
                 *reinterpret_cast<uint2 *>(orow + c) = make_uint2(pack2<BF16>(y0, y1), pack2<BF16>(y2, y3));
@@ -429,15 +434,17 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 
 template <int D, int NQ, int NWAVE, int WPS>
 hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                    const float *k_scale, const float *v_scale, void *out, int BH, int N, bool causal,
-                    float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
+                    const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                    bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
     constexpr int BM = 16 * NQ * NWAVE;
-    const dim3 grid = causal ? dim3(BH, cdiv(N, BM)) : dim3(cdiv(N, BM), BH);
-    const int nT = cdiv(N, kW), nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
+    const int BH = B * Hq;
+    const dim3 grid = causal ? dim3(BH, cdiv(Nq, BM)) : dim3(cdiv(Nq, BM), BH);
+    const int nT = cdiv(Nk, kW), nQ = cdiv(Nq, kBQ), nK = cdiv(Nk, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
-#define SAGE_LAUNCH(C, BF)                                                                                \
-    attn_kernel<D, NQ, NWAVE, WPS, C, BF><<<grid, NWAVE * 64, 0, stream>>>(q_i8, k_i8, v_fp8, q_scale, k_scale, \
-                                                                         v_scale, o16, N, nT, nQ, nK, sm_scale, log2_pr)
+#define SAGE_LAUNCH(C, BF)                                                                                   \
+    attn_kernel<D, NQ, NWAVE, WPS, C, BF><<<grid, NWAVE * 64, 0, stream>>>(q_i8, k_i8, v_fp8, q_scale, k_scale,  \
+                                                                         v_scale, o16, Nq, Nk, nT, nQ, nK, Hq, \
+                                                                         Hq / Hkv, sm_scale, log2_pr)
     if (causal) {
         if (bf16_out) SAGE_LAUNCH(true, true); else SAGE_LAUNCH(true, false);
     } else {
@@ -450,17 +457,17 @@ hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8
 }  // namespace
 
 hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                       const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
-                       bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
+                       const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                       int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
     const float log2_pr = (float)log2((double)p_r);
     // 16 query rows per wavefront, 8 wavefronts (128 rows) per workgroup, 4 wavefronts per SIMD:
     // the fastest of the measured shapes for both head dimensions (the kernel is bound by vector
     // ALU issue, and more resident wavefronts overlap MFMA and VALU work better than wider tiles)
     if (d == 128)
-        return launch_d<128, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale,
-                                      log2_pr, bf16_out, stream);
-    return launch_d<64, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B * H, N, causal, sm_scale, log2_pr,
-                                 bf16_out, stream);
+        return launch_d<128, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal,
+                                      sm_scale, log2_pr, bf16_out, stream);
+    return launch_d<64, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal, sm_scale,
+                                 log2_pr, bf16_out, stream);
 }
 
 }  // namespace sage

@@ -24,15 +24,16 @@ struct QuantScratch {
 QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d);
 
 // stage 1 launches (sage_quant.hip)
-hipError_t launch_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
-                           float *k_scale, float *k_mean, int B, int H, int N, int d, bool bf16,
-                           hipStream_t stream, const QuantScratch &ws);
+hipError_t launch_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int N, int d, bool bf16,
+                          hipStream_t stream);
+hipError_t launch_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H, int N, int d,
+                          bool bf16, hipStream_t stream, const QuantScratch &ws);
 hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
 
-// stage 2 launch (sage_attn.hip)
+// stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys
 hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                       const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
-                       bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream);
+                       const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                       int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream);
 
 }  // namespace sage

@@ -250,16 +250,21 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <bool BF16, int D>
-hipError_t quant_qk_impl(const uint16_t *q, const uint16_t *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
-                         float *k_scale, float *k_mean, int BH, int N, hipStream_t stream,
-                         const QuantScratch &ws) {
+hipError_t quant_q_impl(const uint16_t *q, int8_t *q_i8, float *q_scale, int BH, int N, hipStream_t stream) {
+    const int nQ = cdiv(N, kBQ);
+    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
+    return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t quant_k_impl(const uint16_t *k, int8_t *k_i8, float *k_scale, float *k_mean, int BH, int N,
+                        hipStream_t stream, const QuantScratch &ws) {
     const int chunks = cdiv(N, kStatRows);
-    const int nQ = cdiv(N, kBQ), nK = cdiv(N, kBK);
+    const int nK = cdiv(N, kBK);
     colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, N, chunks, ws.k_sum_part, nullptr);
     finalize_mean_kernel<<<BH, 1024, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
     // K right after its statistics pass: its second read can still be served by the last-level cache
     quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, k_mean, k_i8, k_scale, N, nK);
-    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
     return hipGetLastError();
 }
 
@@ -292,17 +297,26 @@ QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d) {
     return ws;
 }
 
-hipError_t launch_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale,
-                           float *k_scale, float *k_mean, int B, int H, int N, int d, bool bf16,
-                           hipStream_t stream, const QuantScratch &ws) {
-    const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k);
+hipError_t launch_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int N, int d, bool bf16,
+                          hipStream_t stream) {
+    const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const int BH = B * H;
-    if (d == 128) {
-        return bf16 ? quant_qk_impl<true, 128>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws)
-                    : quant_qk_impl<false, 128>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws);
-    }
-    return bf16 ? quant_qk_impl<true, 64>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws)
-                : quant_qk_impl<false, 64>(q16, k16, q_i8, k_i8, q_scale, k_scale, k_mean, BH, N, stream, ws);
+    if (d == 128)
+        return bf16 ? quant_q_impl<true, 128>(q16, q_i8, q_scale, BH, N, stream)
+                    : quant_q_impl<false, 128>(q16, q_i8, q_scale, BH, N, stream);
+    return bf16 ? quant_q_impl<true, 64>(q16, q_i8, q_scale, BH, N, stream)
+                : quant_q_impl<false, 64>(q16, q_i8, q_scale, BH, N, stream);
+}
+
+hipError_t launch_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H, int N, int d,
+                          bool bf16, hipStream_t stream, const QuantScratch &ws) {
+    const uint16_t *k16 = static_cast<const uint16_t *>(k);
+    const int BH = B * H;
+    if (d == 128)
+        return bf16 ? quant_k_impl<true, 128>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws)
+                    : quant_k_impl<false, 128>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws);
+    return bf16 ? quant_k_impl<true, 64>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws)
+                : quant_k_impl<false, 64>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws);
 }
 
 hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,

@@ -278,3 +278,78 @@ def test_accuracy_against_full_precision_is_in_a_plausible_band():
         ref, _ = brute_force(q, k, v, base.sm_scale, base.causal)
         assert wl.cos_sim(ref, out) > cos_min
         assert wl.rel_l1(ref, out) < l1_max
+
+
+# --------------------------------------------------------------------------
+# N_q != N_k (cross attention, end-aligned causal mask) and grouped-query attention
+# --------------------------------------------------------------------------
+def brute_force_rect(Q, K, V, sm_scale, causal):
+    """softmax(Q K^T * sm_scale) V with Nq != Nk; causal: key n visible to query r iff n <= r + Nk - Nq."""
+    Q, K, V = (np.asarray(x, dtype=np.float64) for x in (Q, K, V))
+    S = (Q @ K.T) * sm_scale
+    if causal:
+        Nq, Nk = S.shape
+        S = np.where(np.arange(Nk)[None, :] <= np.arange(Nq)[:, None] + (Nk - Nq), S, -np.inf)
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    return P @ V, P
+
+
+@pytest.mark.parametrize("Nq,Nk,w", [(1, 40, 16), (7, 50, 16), (33, 64, 128), (20, 20, 8), (50, 13, 4)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_rectangular_online_softmax_equals_definition(Nq, Nk, w, causal):
+    if causal and Nk < Nq:
+        pytest.skip("the end-aligned causal mask needs Nk >= Nq")
+    rng = np.random.default_rng(Nq * 100 + Nk)
+    d = 8
+    Q = rng.standard_normal((Nq, d)) * 2
+    K = rng.standard_normal((Nk, d)) * 2
+    V = rng.standard_normal((Nk, d))
+    out, P = oracle.attn_rows_fp(Q, K, V, causal=causal, sm_scale=0.4, w=w, want_p=True)
+    ref, Pref = brute_force_rect(Q, K, V, 0.4, causal)
+    assert np.abs(out - ref).max() <= 1e-12 * max(1.0, np.abs(ref).max())
+    assert np.abs(P - Pref).max() <= 1e-13
+
+
+@pytest.mark.parametrize("Nq,Nk,bq,bk,w", [(16, 64, 16, 8, 16), (10, 50, 16, 8, 16), (64, 260, 128, 64, 128), (2, 36, 8, 4, 12)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_rectangular_quantised_pipeline_is_exact_when_lossless(Nq, Nk, bq, bk, w, causal):
+    """Queries of a lossless problem against a longer lossless key set, brute-forced."""
+    Qfull, K, V, t = _lossless_problem(Nk, bq, bk, (0, 1), (0,), True, seed=Nq + Nk)
+    # any Nq rows keep the construction valid as long as every Q block holds a +-127: take whole
+    # rows from the start (block scales then follow the construction's order)
+    Q = Qfull[:Nq]
+    sm_scale = math.log(2.0) / 127.0
+    qc, qs = oracle.quant_int8(Q.astype(np.float32), None, bq)
+    kmu = oracle.k_mean(K.astype(np.float32))
+    kc, ks = oracle.quant_int8(K.astype(np.float32), kmu, bk)
+    vc, vs = oracle.quant_v(V.astype(np.float32), 4.5)
+    assert np.array_equal(qc.astype(np.float64) * qs[np.arange(Nq) // bq, None], Q)
+    out, P = oracle.attn_rows(qc, kc, vc, qs, ks, vs, causal=causal, sm_scale=sm_scale, bq=bq, bk=bk, w=w,
+                              out_dtype=None, want_p=True)
+    ref, Pref = brute_force_rect(Q, K, V, sm_scale, causal)
+    assert np.abs(out - ref).max() <= 1e-12 * np.abs(ref).max()
+    assert np.abs(P - Pref).max() <= 1e-13
+
+
+def test_rectangular_call_matches_the_tail_rows_of_self_attention():
+    """With Nk - Nq a multiple of the Q block, the last Nq queries of a self-attention problem are
+    the same computation as the rectangular call (same Q blocks, same end-aligned mask)."""
+    (q, k, v), base = _head(1, 384)
+    quant = oracle.quantize_head(q, k, v)
+    full = oracle.attn_rows(quant["q_codes"], quant["k_codes"], quant["v_codes"], quant["q_scale"], quant["k_scale"],
+                            quant["v_scale"], causal=True, sm_scale=base.sm_scale, out_dtype="fp16")
+    tail = oracle.attn_rows(quant["q_codes"][256:], quant["k_codes"], quant["v_codes"], quant["q_scale"][2:],
+                            quant["k_scale"], quant["v_scale"], causal=True, sm_scale=base.sm_scale, out_dtype="fp16")
+    assert np.array_equal(full[256:], tail)
+
+
+def test_grouped_query_attention_shares_kv_heads():
+    base = wl.CONFIGS[0]
+    q, _, _ = wl.generate(base.scaled(B=1, H=4, N=96))
+    _, k, v = wl.generate(base.scaled(B=1, H=2, N=160), seed=7)
+    qf, kf, vf = (wl.as_f32(t) for t in (q, k, v))
+    a = oracle.sage_attention(qf, kf, vf, causal=True, sm_scale=base.sm_scale, out_dtype="fp16")
+    b = oracle.sage_attention(qf, np.repeat(kf, 2, axis=1), np.repeat(vf, 2, axis=1), causal=True,
+                              sm_scale=base.sm_scale, out_dtype="fp16")
+    assert a.shape == (1, 4, 96, 128) and np.array_equal(a, b)
