@@ -2,10 +2,11 @@
 """Benchmark of the SageAttention2++ 8+8 forward pass on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input that
-is already resident in HBM: K smoothing + INT8 quantisation of Q and K, FP8
-quantisation of V, fused attention -- the three C-ABI stage calls that
-``sage_attn_fwd`` makes, on one stream, with HIP events between them so that the
-attention kernel's own duration is measured inside the timed region.
+is already resident in HBM: K smoothing + INT8 quantisation of K, FP8
+quantisation of V, fused attention with the INT8 quantisation of Q in its
+prologue -- the three C-ABI stage calls that ``sage_attn_fwd`` makes, on one
+stream, with HIP events between them so that the attention kernel's own
+duration is measured inside the timed region.
 
 Prints ONE JSON line (metric: attention TOPS = 4*B*H*N^2*d / t, halved when
 causal), with the MFMA roofline of the attention kernel and the CPU oracle's
@@ -43,6 +44,9 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the d=128, N=32768 target workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    ap.add_argument("--staged-q", action="store_true",
+                    help="quantise Q with the stand-alone kernel (sage_quant_q + sage_attn_fwd_quantized) instead "
+                         "of inside the attention kernel; same result bit for bit, for comparison")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of Q (2E bytes read, 2E written) before the timed loop: "
                          "the known-size kernel that FETCH_SIZE / WRITE_SIZE counter runs are scaled by")
@@ -77,7 +81,9 @@ def main():
     out = torch.empty_like(q)
     qws = torch.empty(sage.quant_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=dev)
     # outputs of stage 1, allocated once (nothing is allocated inside the timed region)
-    q_i8, k_i8, q_scale, k_scale, k_mean = sage.sage_quant_qk(q, k, qws)
+    k_i8, k_scale, k_mean = sage.sage_quant_k(k, qws)
+    if args.staged_q:
+        q_i8, q_scale = sage.sage_quant_q(q)
     v_fp8, v_scale = sage.sage_quant_v(v, 4.5, qws)
     L = sage.lib()
     stream = torch.cuda.current_stream()
@@ -85,15 +91,22 @@ def main():
     dt = 1 if cfg.dtype == "bf16" else 0
 
     def step(ev=None):
-        rc = L.sage_quant_qk(q.data_ptr(), k.data_ptr(), q_i8.data_ptr(), k_i8.data_ptr(), q_scale.data_ptr(),
-                             k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d, dt, sp, qws.data_ptr(), qws.numel())
+        rc = L.sage_quant_k(k.data_ptr(), k_i8.data_ptr(), k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d, dt, sp,
+                            qws.data_ptr(), qws.numel())
         rc |= L.sage_quant_v(v.data_ptr(), v_fp8.data_ptr(), v_scale.data_ptr(), 4.5, B, H, N, d, dt, sp,
                              qws.data_ptr(), qws.numel())
+        if args.staged_q:
+            rc |= L.sage_quant_q(q.data_ptr(), q_i8.data_ptr(), q_scale.data_ptr(), B, H, N, d, dt, sp)
         if ev:
             ev[0].record(stream)
-        rc |= L.sage_attn_fwd_quantized(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
-                                        k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, H, N, d,
-                                        int(cfg.causal), sm_scale, 224.0, dt, sp)
+        if args.staged_q:
+            rc |= L.sage_attn_fwd_quantized(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
+                                            k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, H, N, d,
+                                            int(cfg.causal), sm_scale, 224.0, dt, sp)
+        else:
+            rc |= L.sage_attn_fwd_kvquantized_gqa(q.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
+                                                  v_scale.data_ptr(), out.data_ptr(), B, H, H, N, N, d,
+                                                  int(cfg.causal), sm_scale, 224.0, dt, sp)
         if ev:
             ev[1].record(stream)
         if rc != 0:
@@ -119,7 +132,8 @@ def main():
     attn_tops = cfg.ops / (attn_ms * 1e-3) / 1e12
     quant_ms = ms_per_step - attn_ms
     E = B * H * N * d
-    quant_gbs = 9.0 * E / (quant_ms * 1e-3) / 1e9 if quant_ms > 0 else None
+    # K and V: 2 bytes read + 1 byte written per element (Q is quantised inside the attention kernel)
+    quant_gbs = (9.0 if args.staged_q else 6.0) * E / (quant_ms * 1e-3) / 1e9 if quant_ms > 0 else None
 
     result = {
         "metric": "attention TOPS (4*B*H*N^2*d/s, halved when causal), quantisation + attention",
@@ -139,7 +153,8 @@ def main():
                                + (f", {cfg.k_outlier_channels} K outlier channels x20" if cfg.k_outlier_channels else ""),
                    "p_r": 224.0, "v_r": 4.5, "bq": 128, "bk": 64, "w": 128},
         "roofline": {
-            "kernel": "attn_kernel (fused INT8 QK^T + softmax + FP8 PV)",
+            "kernel": "attn_kernel (" + ("" if args.staged_q else "Q quantisation + ")
+                      + "fused INT8 QK^T + softmax + FP8 PV)",
             "bound": "mfma",
             "achieved": round(attn_tops, 2),
             "peak": PEAK_MFMA_8BIT / 1e12,

@@ -157,9 +157,26 @@ int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const ui
                                 float sm_scale, float p_r, sage_dtype out_dt, void *stream);
 
 /*
- * The whole forward pass: sage_quant_qk + sage_quant_v + sage_attn_fwd_quantized
+ * Fused attention on quantised K^, V^ and UNQUANTISED Q  [Sec. 2.1; Sec. 3.1]: the
+ * per-block INT8 quantisation of Q (blocks of SAGE_BQ rows, delta = max|Q|/127,
+ * round to nearest even) runs in the prologue of the attention kernel, whose
+ * workgroups own exactly one Q block each; Q^ and delta_Q are the same bits
+ * sage_quant_q would produce, but are never written to memory.  Output and every
+ * other argument as for sage_attn_fwd_quantized_gqa;
+ *   q        device, [B,Hq,Nq,d] of `dt`, 16-byte aligned                 (in)
+ *   out      device, [B,Hq,Nq,d] of `dt`                                  (out)
+ * Returns SAGE_EINVAL / SAGE_EHIP like the other stage-2 calls.
+ */
+int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8_t *v_fp8,
+                                  const float *k_scale, const float *v_scale, void *out,
+                                  int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal,
+                                  float sm_scale, float p_r, sage_dtype dt, void *stream);
+
+/*
+ * The whole forward pass: sage_quant_k + sage_quant_v + sage_attn_fwd_kvquantized_gqa
  * with the default ranges (P_r = 224, V_r = 4.5), intermediates in `workspace`
- * (device, >= sage_workspace_bytes(), 256-byte aligned).
+ * (device, >= sage_workspace_bytes(), 256-byte aligned).  The result is bit-identical
+ * to sage_quant_qk + sage_quant_v + sage_attn_fwd_quantized.
  *   q, k, v  device, [B,H,N,d] of `dt`                                   (in)
  *   out      device, [B,H,N,d] of `dt`                                   (out)
  */
@@ -169,7 +186,7 @@ int sage_attn_fwd(const void *q, const void *k, const void *v, void *out,
 
 /*
  * The whole forward pass for grouped-query / cross attention: sage_quant_k +
- * sage_quant_v + sage_quant_q + sage_attn_fwd_quantized_gqa, default ranges,
+ * sage_quant_v + sage_attn_fwd_kvquantized_gqa, default ranges,
  * workspace >= sage_workspace_bytes_gqa().
  */
 int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out,

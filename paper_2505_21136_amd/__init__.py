@@ -18,15 +18,16 @@ from . import build as _build
 __all__ = [
     "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
-    "sage_attn_fwd_quantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "workspace_bytes_gqa",
+    "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
+    "workspace_bytes_gqa",
     "v_fp8_to_token_major", "EXPORTS",
 ]
 
 SAGE_F16, SAGE_BF16 = 0, 1
 EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_workspace_bytes",
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
-           "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa", "sage_attn_fwd",
-           "sage_attn_fwd_gqa"]
+           "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
+           "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa"]
 
 
 class SageError(RuntimeError):
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.sage_quant_k.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_attn_fwd_quantized_gqa.restype = i
         L.sage_attn_fwd_quantized_gqa.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, vp]
+        L.sage_attn_fwd_kvquantized_gqa.restype = i
+        L.sage_attn_fwd_kvquantized_gqa.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, vp]
         L.sage_attn_fwd_gqa.restype = i
         L.sage_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, i, vp, sz]
         L.sage_quant_qk.restype = i
@@ -217,6 +220,23 @@ def sage_attn_fwd_quantized_gqa(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, *,
     _check(lib().sage_attn_fwd_quantized_gqa(q_i8.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), q_scale.data_ptr(),
                                              k_scale.data_ptr(), v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq,
                                              Nk, d, int(causal), float(sm_scale), float(p_r), _dt(out), _stream()))
+    return out
+
+
+def sage_attn_fwd_kvquantized_gqa(q, k_i8, v_fp8, k_scale, v_scale, *, causal: bool, sm_scale: float,
+                                  p_r: float = 224.0, out: torch.Tensor | None = None):
+    """Unquantised q [B,Hq,Nq,d] (quantised inside the kernel) against k_i8 [B,Hkv,Nk,d] / v_fp8."""
+    _dev(q, k_i8, v_fp8, k_scale, v_scale)
+    B, Hq, Nq, d = q.shape
+    _, Hkv, Nk, _ = k_i8.shape
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    if out.dtype != q.dtype:
+        raise SageError("out must have q's dtype")
+    _check(lib().sage_attn_fwd_kvquantized_gqa(q.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
+                                               v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d, int(causal),
+                                               float(sm_scale), float(p_r), _dt(q), _stream()))
     return out
 
 

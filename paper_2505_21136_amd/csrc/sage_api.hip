@@ -28,26 +28,23 @@ int from_hip(hipError_t e) {
 
 // Carving of the sage_attn_fwd workspace.
 struct FwdWorkspace {
-    int8_t *q_i8, *k_i8;
+    int8_t *k_i8;
     uint8_t *v_fp8;
-    float *q_scale, *k_scale, *v_scale, *k_mean;
+    float *k_scale, *v_scale, *k_mean;
     void *quant;
     size_t quant_bytes;
     size_t bytes;
 };
 FwdWorkspace fwd_layout(void *base, int B, int Hq, int Hkv, int Nq, int Nk, int d) {
-    const size_t Eq = (size_t)B * Hq * Nq * d, Ek = (size_t)B * Hkv * Nk * d, BHk = (size_t)B * Hkv;
+    (void)Hq, (void)Nq;  // Q is quantised inside the attention kernel: nothing of it is staged
+    const size_t Ek = (size_t)B * Hkv * Nk * d, BHk = (size_t)B * Hkv;
     char *p = static_cast<char *>(base);
     size_t off = 0;
     FwdWorkspace w;
-    w.q_i8 = reinterpret_cast<int8_t *>(p + off);
-    off += align256(Eq);
     w.k_i8 = reinterpret_cast<int8_t *>(p + off);
     off += align256(Ek);
     w.v_fp8 = reinterpret_cast<uint8_t *>(p + off);
     off += align256(sage_v_fp8_bytes(B, Hkv, Nk, d));
-    w.q_scale = reinterpret_cast<float *>(p + off);
-    off += align256((size_t)B * Hq * sage::cdiv(Nq, sage::kBQ) * sizeof(float));
     w.k_scale = reinterpret_cast<float *>(p + off);
     off += align256(BHk * sage::cdiv(Nk, sage::kBK) * sizeof(float));
     w.v_scale = reinterpret_cast<float *>(p + off);
@@ -160,9 +157,22 @@ int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const ui
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
     if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
-    return from_hip(sage::launch_attn(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
+    return from_hip(sage::launch_attn(q_i8, false, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
                                       causal != 0, sm_scale, p_r, out_dt == SAGE_BF16,
                                       static_cast<hipStream_t>(stream)));
+}
+
+int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                                  const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d,
+                                  int causal, float sm_scale, float p_r, sage_dtype dt, void *stream) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !k_i8 || !v_fp8 || !k_scale || !v_scale || !out) return SAGE_EINVAL;
+    if (!aligned16(q) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
+        return SAGE_EINVAL;
+    if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
+    if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
+    return from_hip(sage::launch_attn(q, true, k_i8, v_fp8, nullptr, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
+                                      causal != 0, sm_scale, p_r, dt == SAGE_BF16, static_cast<hipStream_t>(stream)));
 }
 
 int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
@@ -185,10 +195,9 @@ int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out, in
     if (rc != SAGE_OK) return rc;
     rc = sage_quant_v(v, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk, d, dt, stream, w.quant, w.quant_bytes);
     if (rc != SAGE_OK) return rc;
-    rc = sage_quant_q(q, w.q_i8, w.q_scale, B, Hq, Nq, d, dt, stream);
-    if (rc != SAGE_OK) return rc;
-    return sage_attn_fwd_quantized_gqa(w.q_i8, w.k_i8, w.v_fp8, w.q_scale, w.k_scale, w.v_scale, out, B, Hq, Hkv, Nq,
-                                       Nk, d, causal, sm_scale, 224.0f, dt, stream);
+    // Q is quantised inside the attention kernel: Q^ and delta_Q never touch memory
+    return sage_attn_fwd_kvquantized_gqa(q, w.k_i8, w.v_fp8, w.k_scale, w.v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal,
+                                         sm_scale, 224.0f, dt, stream);
 }
 
 int sage_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H, int N, int d, int causal,

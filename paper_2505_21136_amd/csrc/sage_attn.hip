@@ -82,6 +82,13 @@ __device__ __forceinline__ float rowgroup_sum(float x) {
     return a + b;
 }
 
+// 16-bit input value (bits in the low half of u) -> binary32, exact
+template <bool BF16>
+__device__ __forceinline__ float to_f32(uint32_t u) {
+    if constexpr (BF16) return __builtin_bit_cast(float, u << 16);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)u);
+}
+
 template <bool BF16>
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
     if constexpr (BF16) {
@@ -206,9 +213,14 @@ __device__ __forceinline__ void issue_tile_copy(uint8_t *dst, __amdgpu_buffer_rs
 // ALU), so the two pipes of every SIMD are busy at the same time instead of colliding.  A slot
 // ends with a workgroup barrier.  Tile copies for K^(j+1) and V^(j) are issued at the start of
 // slot 2j and are needed from slot 2j+2 on: two slots of latency to hide them.
-template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16>
+//
+// QRAW: Q arrives unquantised (16-bit, the output's type) and the workgroup, whose 128 rows are
+// exactly one Q quantisation block, quantises it in its prologue (paper Sec. 2.1: per-block INT8,
+// delta = max|Q| / 127) with the same binary32 operations as the stand-alone quantiser, so codes
+// and scale are the same bits; Q^ and delta_Q then never touch memory.
+template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW>
 __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
-    const int8_t *__restrict__ Qc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
+    const void *__restrict__ Qsrc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
     uint16_t *__restrict__ out, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq, int group, float sm_scale,
     float log2_pr) {
@@ -222,6 +234,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     static_assert(TILE / 16 % NTHR == 0, "tile chunks must divide over the threads");
     __shared__ __attribute__((aligned(1024))) uint8_t ldsK[2][TILE];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsV[2][TILE];
+    __shared__ float q_wave_max[NWAVE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -240,7 +253,6 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // causal mask aligned to the end of both sequences: key n visible to query r iff n <= r + shift
     const int shift = Nk - Nq;
 
-    const int8_t *Qh = Qc + (size_t)bh * Nq * D;
     const int8_t *Kh = Kc + (size_t)bhk * Nk * D;
     const uint8_t *Vh = Vt + (size_t)bhk * nT * D * 128;
     // buffer descriptors bounded to this head: rows >= Nk of K^ read as zero
@@ -270,18 +282,43 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
     issue_tile_copy<D, NWAVE, CPY>(ldsK[0], k_rsrc, k_voff, wave, 0);
 
+    // the lane's B operand of S^T = K^ Q^T: 16 consecutive channels (64*ch + 16*g ..) of query row lq
     v4i qreg[NQ][KC];
+    uint4 qraw[NQ][KC][2];  // QRAW: the same 16 channels as 16-bit values
+    if constexpr (QRAW) {
+        static_assert(BM == kBQ, "a workgroup must own exactly one Q quantisation block");
+        const uint16_t *Qh = static_cast<const uint16_t *>(Qsrc) + (size_t)bh * Nq * D;
+        float amax = 0.0f;
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-        const int r = row0 + qt * 16 + lq;
+        for (int qt = 0; qt < NQ; ++qt) {
+            const int r = row0 + qt * 16 + lq;
 #pragma unroll
-        for (int ch = 0; ch < KC; ++ch) {
-            v4i z = {0, 0, 0, 0};
-            qreg[qt][ch] = r < Nq ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
+            for (int ch = 0; ch < KC; ++ch)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    qraw[qt][ch][h] = r < Nq ? *reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + ch * 64 + g * 16 + h * 8)
+                                             : make_uint4(0u, 0u, 0u, 0u);
+                    const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(w[i] & 0xffffu)), fabsf(to_f32<BF16>(w[i] >> 16))));
+                }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        if (lane == 0) q_wave_max[wave] = amax;
+    } else {
+        const int8_t *Qh = static_cast<const int8_t *>(Qsrc) + (size_t)bh * Nq * D;
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt) {
+            const int r = row0 + qt * 16 + lq;
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch) {
+                v4i z = {0, 0, 0, 0};
+                qreg[qt][ch] = r < Nq ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
+            }
         }
     }
-    // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
-    const double cq = (double)dq[(size_t)bh * nQblk + min(row0, Nq - 1) / kBQ] * (double)sm_scale * 1.4426950408889634;
     float cvec = 0.0f;  // lane i: constant of K block 64*(j/32) + i, refreshed every 32 steps
     const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
@@ -303,6 +340,38 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): K^(0) has landed
     __syncthreads();
+
+    // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
+    float delta_q;
+    if constexpr (QRAW) {
+        float a = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) a = fmaxf(a, q_wave_max[w]);
+        const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
+        delta_q = a / 127.0f;
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        uint32_t packed = 0u;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t u = w[2 * hh + (i >> 1)];
+                            const float x = to_f32<BF16>((i & 1) ? (u >> 16) : (u & 0xffffu));
+                            packed |= ((uint32_t)(int)__builtin_rintf(x * rcp) & 0xffu) << (8 * i);
+                        }
+                        qreg[qt][ch][2 * h + hh] = (int)packed;
+                    }
+                }
+    } else {
+        delta_q = dq[(size_t)bh * nQblk + min(row0, Nq - 1) / kBQ];
+    }
+    const double cq = (double)delta_q * (double)sm_scale * 1.4426950408889634;
 
     // start of an even slot 2*jj: fetch K^(jj+1) and V^(jj)
     auto issue_copies = [&](int jj) {
@@ -433,7 +502,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 }
 
 template <int D, int NQ, int NWAVE, int WPS>
-hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+hipError_t launch_d(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                     const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
                     bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
     constexpr int BM = 16 * NQ * NWAVE;
@@ -441,22 +510,25 @@ hipError_t launch_d(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8
     const dim3 grid = causal ? dim3(BH, cdiv(Nq, BM)) : dim3(cdiv(Nq, BM), BH);
     const int nT = cdiv(Nk, kW), nQ = cdiv(Nq, kBQ), nK = cdiv(Nk, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
-#define SAGE_LAUNCH(C, BF)                                                                                   \
-    attn_kernel<D, NQ, NWAVE, WPS, C, BF><<<grid, NWAVE * 64, 0, stream>>>(q_i8, k_i8, v_fp8, q_scale, k_scale,  \
-                                                                         v_scale, o16, Nq, Nk, nT, nQ, nK, Hq, \
-                                                                         Hq / Hkv, sm_scale, log2_pr)
+#define SAGE_LAUNCH(C, BF, QR)                                                                              \
+    attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR><<<grid, NWAVE * 64, 0, stream>>>(q, k_i8, v_fp8, q_scale, k_scale, \
+                                                                             v_scale, o16, Nq, Nk, nT, nQ, nK,  \
+                                                                             Hq, Hq / Hkv, sm_scale, log2_pr)
+#define SAGE_LAUNCH_Q(C, BF) \
+    if (q_raw) SAGE_LAUNCH(C, BF, true); else SAGE_LAUNCH(C, BF, false)
     if (causal) {
-        if (bf16_out) SAGE_LAUNCH(true, true); else SAGE_LAUNCH(true, false);
+        if (bf16_out) { SAGE_LAUNCH_Q(true, true); } else { SAGE_LAUNCH_Q(true, false); }
     } else {
-        if (bf16_out) SAGE_LAUNCH(false, true); else SAGE_LAUNCH(false, false);
+        if (bf16_out) { SAGE_LAUNCH_Q(false, true); } else { SAGE_LAUNCH_Q(false, false); }
     }
+#undef SAGE_LAUNCH_Q
 #undef SAGE_LAUNCH
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+hipError_t launch_attn(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                        const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
                        int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
     const float log2_pr = (float)log2((double)p_r);
@@ -464,9 +536,9 @@ hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_
     // the fastest of the measured shapes for both head dimensions (the kernel is bound by vector
     // ALU issue, and more resident wavefronts overlap MFMA and VALU work better than wider tiles)
     if (d == 128)
-        return launch_d<128, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal,
+        return launch_d<128, 1, 8, 4>(q, q_raw, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal,
                                       sm_scale, log2_pr, bf16_out, stream);
-    return launch_d<64, 1, 8, 4>(q_i8, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal, sm_scale,
+    return launch_d<64, 1, 8, 4>(q, q_raw, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal, sm_scale,
                                  log2_pr, bf16_out, stream);
 }
 

@@ -31,8 +31,10 @@ hipError_t launch_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_
 hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
 
-// stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys
-hipError_t launch_attn(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+// stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys.
+// q_raw = false: q is Q^ (int8) with scales q_scale; q_raw = true: q is the unquantised 16-bit Q
+// (type of the output), quantised inside the kernel, q_scale unused.
+hipError_t launch_attn(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                        const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
                        int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream);
 

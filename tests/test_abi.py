@@ -36,7 +36,10 @@ def test_params_and_sizes():
         qb, wb = sage.quant_workspace_bytes(*shape), sage.workspace_bytes(*shape)
         B, H, N, d = shape
         assert qb > 0 and qb % 256 == 0 and wb % 256 == 0
-        assert wb >= qb + 2 * B * H * N * d + sage.v_fp8_bytes(*shape)
+        # K^ and V^ are staged; Q is quantised inside the attention kernel and needs no space
+        assert wb >= qb + B * H * N * d + sage.v_fp8_bytes(*shape)
+        if B * H * N * d >= 1 << 16:   # (tiny shapes: the 256-byte paddings dominate)
+            assert wb < qb + 2 * B * H * N * d + sage.v_fp8_bytes(*shape)
     # unsupported shapes report size 0
     assert sage.workspace_bytes(1, 1, 16, 96) == 0 and sage.v_fp8_bytes(0, 1, 16, 64) == 0
 
