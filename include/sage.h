@@ -193,6 +193,26 @@ int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out,
                       int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale,
                       void *stream, sage_dtype dt, void *workspace, size_t workspace_bytes);
 
+/*
+ * The whole forward pass on strided tensors  [same passages as sage_attn_fwd]: the
+ * four tensors may be any views whose channel dimension is contiguous, e.g. the
+ * token-major [B,N,H,d] layout or slices of a packed QKV projection; nothing is
+ * copied, the kernels read and write through the strides.
+ *   *_strides  host pointers to three ELEMENT strides {batch, head, token}; NULL means
+ *              contiguous [B,H,N,d].  Inputs: every stride >= 0 and a multiple of 8
+ *              (16-byte aligned rows; 0 broadcasts that dimension).  Output: the same,
+ *              and no two rows may overlap.  SAGE_EINVAL otherwise.
+ * All other arguments, the workspace and the result (bit-identical to sage_attn_fwd_gqa
+ * on contiguous copies) as for sage_attn_fwd_gqa.  The stride arrays are read before the
+ * call returns.
+ */
+int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out,
+                          int B, int Hq, int Hkv, int Nq, int Nk, int d,
+                          const int64_t *q_strides, const int64_t *k_strides,
+                          const int64_t *v_strides, const int64_t *out_strides,
+                          int causal, float sm_scale, void *stream, sage_dtype dt,
+                          void *workspace, size_t workspace_bytes);
+
 #ifdef __cplusplus
 }
 #endif

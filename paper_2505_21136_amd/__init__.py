@@ -19,7 +19,7 @@ __all__ = [
     "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
-    "workspace_bytes_gqa",
+    "sage_attn_fwd_strided", "workspace_bytes_gqa",
     "v_fp8_to_token_major", "EXPORTS",
 ]
 
@@ -27,7 +27,7 @@ SAGE_F16, SAGE_BF16 = 0, 1
 EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_workspace_bytes",
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
-           "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa"]
+           "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided"]
 
 
 class SageError(RuntimeError):
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.sage_attn_fwd_kvquantized_gqa.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, vp]
         L.sage_attn_fwd_gqa.restype = i
         L.sage_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, i, vp, sz]
+        L.sage_attn_fwd_strided.restype = i
+        L.sage_attn_fwd_strided.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, i, f, vp, i, vp, sz]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -255,6 +257,49 @@ def sage_attn_fwd_gqa(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torc
     ws = workspace if workspace is not None else _workspace(need, q.device)
     _check(lib().sage_attn_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d,
                                    int(causal), float(sm_scale), _stream(), _dt(q), ws.data_ptr(), ws.numel()))
+    return out
+
+
+def _bhn_strides(t: torch.Tensor, layout: str):
+    """(B, H, N, d) and the ctypes {batch, head, token} element strides of a 4-D view."""
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise SageError("strided tensors must be 4-D with a contiguous last (channel) dimension")
+    if layout == "bhnd":
+        (B, H, N, d), (sb, sh, sn) = t.shape, t.stride()[:3]
+    elif layout == "bnhd":
+        (B, N, H, d), (sb, sn, sh) = t.shape, t.stride()[:3]
+    else:
+        raise SageError(f"unknown layout {layout!r}: 'bhnd' or 'bnhd'")
+    return (B, H, N, d), (ctypes.c_int64 * 3)(sb, sh, sn)
+
+
+def sage_attn_fwd_strided(q, k, v, *, causal: bool, sm_scale: float = 0.0, layout: str = "bhnd",
+                          out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """Whole forward pass on views (no copies): `layout` names the order of the tensors' dimensions,
+    'bhnd' ([B,H,N,d]) or 'bnhd' ([B,N,H,d]); any strides with a contiguous channel dimension are accepted
+    (transposed views, slices of a packed QKV tensor).  `out` defaults to a new contiguous tensor of q's
+    shape in the same dimension order."""
+    for t in (q, k, v):
+        if not t.is_cuda:
+            raise SageError("libsage needs device tensors (no CPU path exists)")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise SageError("k and v must have the dtype of q")
+    (B, Hq, Nq, d), qs = _bhn_strides(q, layout)
+    (Bk, Hkv, Nk, dk), ks = _bhn_strides(k, layout)
+    (Bv, Hv, Nv, dv), vs = _bhn_strides(v, layout)
+    if (Bk, dk) != (B, d) or (Bv, Hv, Nv, dv) != (Bk, Hkv, Nk, dk):
+        raise SageError("k and v must share a shape and q's batch and head dimension")
+    if out is None:
+        out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
+    if not out.is_cuda or out.dtype != q.dtype or out.shape != q.shape:
+        raise SageError("out must be a device tensor of q's shape and dtype")
+    _, os_ = _bhn_strides(out, layout)
+    need = workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d)
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    _check(lib().sage_attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d,
+                                       ctypes.addressof(qs), ctypes.addressof(ks), ctypes.addressof(vs),
+                                       ctypes.addressof(os_), int(causal), float(sm_scale), _stream(), _dt(q),
+                                       ws.data_ptr(), ws.numel()))
     return out
 
 

@@ -20,6 +20,39 @@ bool gqa_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal) {
     return shape_ok(B, Hq, Nq, d) && shape_ok(B, Hkv, Nk, d) && Hq % Hkv == 0 && (!causal || Nk >= Nq);
 }
 bool dtype_ok(sage_dtype dt) { return dt == SAGE_F16 || dt == SAGE_BF16; }
+
+// Caller-supplied element strides (batch, head, token); NULL selects contiguous [B,H,N,d].
+// Inputs: non-negative multiples of 8 elements (rows stay 16-byte aligned; 0 broadcasts).
+bool read_strides(const int64_t *s, int H, int N, int d, sage::Strides *out) {
+    if (!s) {
+        *out = sage::contiguous_bhnd(H, N, d);
+        return true;
+    }
+    for (int i = 0; i < 3; ++i)
+        if (s[i] < 0 || s[i] % 8 != 0) return false;
+    *out = sage::Strides{s[0], s[1], s[2]};
+    return true;
+}
+// Output: additionally no two (b, h, n) rows may overlap -- sorted by stride, every stride must
+// cover the extent of the next smaller one (dimensions of extent 1 do not matter).
+bool write_strides_ok(const sage::Strides &st, int B, int H, int N, int d) {
+    int64_t stride[3] = {st.b, st.h, st.n};
+    int64_t extent[3] = {B, H, N};
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 3; ++j)
+            if (stride[j] < stride[i]) {
+                const int64_t ts = stride[i], te = extent[i];
+                stride[i] = stride[j], extent[i] = extent[j];
+                stride[j] = ts, extent[j] = te;
+            }
+    int64_t span = d;  // elements covered by everything below the current dimension
+    for (int i = 0; i < 3; ++i) {
+        if (extent[i] == 1) continue;
+        if (stride[i] < span) return false;
+        span = stride[i] * extent[i];
+    }
+    return true;
+}
 int from_hip(hipError_t e) {
     if (e == hipSuccess) return SAGE_OK;
     g_last_hip_error = e;
@@ -106,7 +139,7 @@ int sage_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int 
                  void *stream) {
     if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
     if (!q || !q_i8 || !q_scale || !aligned16(q) || !aligned16(q_i8)) return SAGE_EINVAL;
-    return from_hip(sage::launch_quant_q(q, q_i8, q_scale, B, H, N, d, dt == SAGE_BF16,
+    return from_hip(sage::launch_quant_q(q, sage::contiguous_bhnd(H, N, d), q_i8, q_scale, B, H, N, d, dt == SAGE_BF16,
                                          static_cast<hipStream_t>(stream)));
 }
 
@@ -117,8 +150,8 @@ int sage_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
         return SAGE_EWORKSPACE;
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
-    return from_hip(sage::launch_quant_k(k, k_i8, k_scale, k_mean, B, H, N, d, dt == SAGE_BF16,
-                                         static_cast<hipStream_t>(stream), ws));
+    return from_hip(sage::launch_quant_k(k, sage::contiguous_bhnd(H, N, d), k_i8, k_scale, k_mean, B, H, N, d,
+                                         dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
 
 int sage_quant_qk(const void *q, const void *k, int8_t *q_i8, int8_t *k_i8, float *q_scale, float *k_scale,
@@ -143,8 +176,8 @@ int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
         return SAGE_EWORKSPACE;
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
-    return from_hip(sage::launch_quant_v(v, v_fp8, v_scale, v_r, B, H, N, d, dt == SAGE_BF16,
-                                         static_cast<hipStream_t>(stream), ws));
+    return from_hip(sage::launch_quant_v(v, sage::contiguous_bhnd(H, N, d), v_fp8, v_scale, v_r, B, H, N, d,
+                                         dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
 
 int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
@@ -157,8 +190,9 @@ int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const ui
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
     if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
-    return from_hip(sage::launch_attn(q_i8, false, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
-                                      causal != 0, sm_scale, p_r, out_dt == SAGE_BF16,
+    const sage::Strides st = sage::contiguous_bhnd(Hq, Nq, d);
+    return from_hip(sage::launch_attn(q_i8, false, st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, st, B, Hq, Hkv, Nq,
+                                      Nk, d, causal != 0, sm_scale, p_r, out_dt == SAGE_BF16,
                                       static_cast<hipStream_t>(stream)));
 }
 
@@ -171,8 +205,10 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
     if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
-    return from_hip(sage::launch_attn(q, true, k_i8, v_fp8, nullptr, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d,
-                                      causal != 0, sm_scale, p_r, dt == SAGE_BF16, static_cast<hipStream_t>(stream)));
+    const sage::Strides st = sage::contiguous_bhnd(Hq, Nq, d);
+    return from_hip(sage::launch_attn(q, true, st, k_i8, v_fp8, nullptr, k_scale, v_scale, out, st, B, Hq, Hkv, Nq, Nk,
+                                      d, causal != 0, sm_scale, p_r, dt == SAGE_BF16,
+                                      static_cast<hipStream_t>(stream)));
 }
 
 int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
@@ -182,22 +218,39 @@ int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_
                                        sm_scale, p_r, out_dt, stream);
 }
 
-int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
-                      int d, int causal, float sm_scale, void *stream, sage_dtype dt, void *workspace,
-                      size_t workspace_bytes) {
+int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out, int B, int Hq, int Hkv, int Nq,
+                          int Nk, int d, const int64_t *q_strides, const int64_t *k_strides, const int64_t *v_strides,
+                          const int64_t *out_strides, int causal, float sm_scale, void *stream, sage_dtype dt,
+                          void *workspace, size_t workspace_bytes) {
     if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
     if (!q || !k || !v || !out) return SAGE_EINVAL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return SAGE_EINVAL;
+    sage::Strides qs, ks, vs, os;
+    if (!read_strides(q_strides, Hq, Nq, d, &qs) || !read_strides(k_strides, Hkv, Nk, d, &ks) ||
+        !read_strides(v_strides, Hkv, Nk, d, &vs) || !read_strides(out_strides, Hq, Nq, d, &os))
+        return SAGE_EINVAL;
+    if (!write_strides_ok(os, B, Hq, Nq, d)) return SAGE_EINVAL;
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d))
         return SAGE_EWORKSPACE;
+    if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
     const FwdWorkspace w = fwd_layout(workspace, B, Hq, Hkv, Nq, Nk, d);
-    int rc = sage_quant_k(k, w.k_i8, w.k_scale, w.k_mean, B, Hkv, Nk, d, dt, stream, w.quant, w.quant_bytes);
-    if (rc != SAGE_OK) return rc;
-    rc = sage_quant_v(v, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk, d, dt, stream, w.quant, w.quant_bytes);
-    if (rc != SAGE_OK) return rc;
+    const sage::QuantScratch qws = sage::quant_scratch_layout(w.quant, B, Hkv, Nk, d);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = dt == SAGE_BF16;
+    hipError_t e = sage::launch_quant_k(k, ks, w.k_i8, w.k_scale, w.k_mean, B, Hkv, Nk, d, bf16, s, qws);
+    if (e == hipSuccess) e = sage::launch_quant_v(v, vs, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk, d, bf16, s, qws);
     // Q is quantised inside the attention kernel: Q^ and delta_Q never touch memory
-    return sage_attn_fwd_kvquantized_gqa(q, w.k_i8, w.v_fp8, w.k_scale, w.v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal,
-                                         sm_scale, 224.0f, dt, stream);
+    if (e == hipSuccess)
+        e = sage::launch_attn(q, true, qs, w.k_i8, w.v_fp8, nullptr, w.k_scale, w.v_scale, out, os, B, Hq, Hkv, Nq, Nk, d,
+                              causal != 0, sm_scale, 224.0f, bf16, s);
+    return from_hip(e);
+}
+
+int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                      int d, int causal, float sm_scale, void *stream, sage_dtype dt, void *workspace,
+                      size_t workspace_bytes) {
+    return sage_attn_fwd_strided(q, k, v, out, B, Hq, Hkv, Nq, Nk, d, nullptr, nullptr, nullptr, nullptr, causal,
+                                 sm_scale, stream, dt, workspace, workspace_bytes);
 }
 
 int sage_attn_fwd(const void *q, const void *k, const void *v, void *out, int B, int H, int N, int d, int causal,

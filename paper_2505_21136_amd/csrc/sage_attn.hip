@@ -222,8 +222,8 @@ template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW>
 __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const void *__restrict__ Qsrc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
-    uint16_t *__restrict__ out, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq, int group, float sm_scale,
-    float log2_pr) {
+    uint16_t *__restrict__ out, Strides q_st, Strides o_st, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq,
+    int group, float sm_scale, float log2_pr) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
     constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
     constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     uint4 qraw[NQ][KC][2];  // QRAW: the same 16 channels as 16-bit values
     if constexpr (QRAW) {
         static_assert(BM == kBQ, "a workgroup must own exactly one Q quantisation block");
-        const uint16_t *Qh = static_cast<const uint16_t *>(Qsrc) + (size_t)bh * Nq * D;
+        const uint16_t *Qh = static_cast<const uint16_t *>(Qsrc) + (bh / Hq) * q_st.b + (bh % Hq) * q_st.h;
         float amax = 0.0f;
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             for (int ch = 0; ch < KC; ++ch)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    qraw[qt][ch][h] = r < Nq ? *reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + ch * 64 + g * 16 + h * 8)
+                    qraw[qt][ch][h] = r < Nq ? *reinterpret_cast<const uint4 *>(Qh + r * q_st.n + ch * 64 + g * 16 + h * 8)
                                              : make_uint4(0u, 0u, 0u, 0u);
                     const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
 #pragma unroll
@@ -308,14 +308,14 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
         if (lane == 0) q_wave_max[wave] = amax;
     } else {
-        const int8_t *Qh = static_cast<const int8_t *>(Qsrc) + (size_t)bh * Nq * D;
+        const int8_t *Qh = static_cast<const int8_t *>(Qsrc) + (bh / Hq) * q_st.b + (bh % Hq) * q_st.h;
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
             const int r = row0 + qt * 16 + lq;
 #pragma unroll
             for (int ch = 0; ch < KC; ++ch) {
                 v4i z = {0, 0, 0, 0};
-                qreg[qt][ch] = r < Nq ? *reinterpret_cast<const v4i *>(Qh + (size_t)r * D + ch * 64 + g * 16) : z;
+                qreg[qt][ch] = r < Nq ? *reinterpret_cast<const v4i *>(Qh + r * q_st.n + ch * 64 + g * 16) : z;
             }
         }
     }
@@ -487,7 +487,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         const float inv = 1.0f / rowgroup_sum(l[qt]);
         const int r = row0 + qt * 16 + lq;
         if (r < Nq) {
-            uint16_t *orow = out + ((size_t)bh * Nq + r) * D;
+            uint16_t *orow = out + (bh / Hq) * o_st.b + (bh % Hq) * o_st.h + r * o_st.n;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 const int c = 16 * ct + 4 * g;
@@ -502,9 +502,9 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 }
 
 template <int D, int NQ, int NWAVE, int WPS>
-hipError_t launch_d(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                    const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
-                    bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
+hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+                    const float *k_scale, const float *v_scale, void *out, Strides o_st, int B, int Hq, int Hkv, int Nq,
+                    int Nk, bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
     constexpr int BM = 16 * NQ * NWAVE;
     const int BH = B * Hq;
     const dim3 grid = causal ? dim3(BH, cdiv(Nq, BM)) : dim3(cdiv(Nq, BM), BH);
@@ -512,8 +512,9 @@ hipError_t launch_d(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t
     uint16_t *o16 = static_cast<uint16_t *>(out);
 #define SAGE_LAUNCH(C, BF, QR)                                                                              \
     attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR><<<grid, NWAVE * 64, 0, stream>>>(q, k_i8, v_fp8, q_scale, k_scale, \
-                                                                             v_scale, o16, Nq, Nk, nT, nQ, nK,  \
-                                                                             Hq, Hq / Hkv, sm_scale, log2_pr)
+                                                                             v_scale, o16, q_st, o_st, Nq, Nk,  \
+                                                                             nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
+                                                                             log2_pr)
 #define SAGE_LAUNCH_Q(C, BF) \
     if (q_raw) SAGE_LAUNCH(C, BF, true); else SAGE_LAUNCH(C, BF, false)
     if (causal) {
@@ -528,18 +529,19 @@ hipError_t launch_d(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t
 
 }  // namespace
 
-hipError_t launch_attn(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                       const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
-                       int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream) {
+hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8,
+                       const float *q_scale, const float *k_scale, const float *v_scale, void *out, Strides o_st, int B,
+                       int Hq, int Hkv, int Nq, int Nk, int d, bool causal, float sm_scale, float p_r, bool bf16_out,
+                       hipStream_t stream) {
     const float log2_pr = (float)log2((double)p_r);
     // 16 query rows per wavefront, 8 wavefronts (128 rows) per workgroup, 4 wavefronts per SIMD:
     // the fastest of the measured shapes for both head dimensions (the kernel is bound by vector
     // ALU issue, and more resident wavefronts overlap MFMA and VALU work better than wider tiles)
     if (d == 128)
-        return launch_d<128, 1, 8, 4>(q, q_raw, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal,
-                                      sm_scale, log2_pr, bf16_out, stream);
-    return launch_d<64, 1, 8, 4>(q, q_raw, k_i8, v_fp8, q_scale, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, causal, sm_scale,
-                                 log2_pr, bf16_out, stream);
+        return launch_d<128, 1, 8, 4>(q, q_raw, q_st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, o_st, B, Hq, Hkv, Nq, Nk,
+                                      causal, sm_scale, log2_pr, bf16_out, stream);
+    return launch_d<64, 1, 8, 4>(q, q_raw, q_st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, o_st, B, Hq, Hkv, Nq, Nk, causal,
+                                 sm_scale, log2_pr, bf16_out, stream);
 }
 
 }  // namespace sage

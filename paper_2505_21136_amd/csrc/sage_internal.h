@@ -14,6 +14,12 @@ constexpr int kStatRows = 256;   // tokens per partial column statistic
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+// Element strides (batch, head, token) of a 4-D tensor whose channels are contiguous.
+struct Strides {
+    int64_t b, h, n;
+};
+inline Strides contiguous_bhnd(int H, int N, int d) { return Strides{(int64_t)H * N * d, (int64_t)N * d, (int64_t)d}; }
+
 // Scratch of the quantisation stage (all offsets 256-byte aligned).
 struct QuantScratch {
     double *k_sum_part;  // [B*H][chunks][d]  partial column sums of K
@@ -24,18 +30,21 @@ struct QuantScratch {
 QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d);
 
 // stage 1 launches (sage_quant.hip)
-hipError_t launch_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int N, int d, bool bf16,
-                          hipStream_t stream);
-hipError_t launch_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H, int N, int d,
-                          bool bf16, hipStream_t stream, const QuantScratch &ws);
-hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
+// (the inputs are read through their strides; every output is contiguous [B,H,...])
+hipError_t launch_quant_q(const void *q, Strides q_st, int8_t *q_i8, float *q_scale, int B, int H, int N, int d,
+                          bool bf16, hipStream_t stream);
+hipError_t launch_quant_k(const void *k, Strides k_st, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H,
+                          int N, int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
+hipError_t launch_quant_v(const void *v, Strides v_st, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
 
 // stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys.
 // q_raw = false: q is Q^ (int8) with scales q_scale; q_raw = true: q is the unquantised 16-bit Q
-// (type of the output), quantised inside the kernel, q_scale unused.
-hipError_t launch_attn(const void *q, bool q_raw, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
-                       const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
-                       int d, bool causal, float sm_scale, float p_r, bool bf16_out, hipStream_t stream);
+// (type of the output), quantised inside the kernel, q_scale unused.  q and out are addressed
+// through their strides; K^, V^ and the scales are contiguous.
+hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
+                       const float *k_scale, const float *v_scale, void *out, Strides o_st, int B, int Hq, int Hkv,
+                       int Nq, int Nk, int d, bool causal, float sm_scale, float p_r, bool bf16_out,
+                       hipStream_t stream);
 
 }  // namespace sage

@@ -42,7 +42,8 @@ __device__ __forceinline__ void unpack8(const uint4 &u, float (&f)[8]) {
 // grid (chunks, B*H), 256 threads; a thread owns 8 adjacent channels.
 // ---------------------------------------------------------------------------
 template <bool BF16, int D, bool IS_V>
-__global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restrict__ X, int N, int chunks,
+__global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restrict__ X, Strides st, int H, int N,
+                                                       int chunks,
                                                        double *__restrict__ sum_part,
                                                        float *__restrict__ max_part) {
     constexpr int LPR = D / 8;     // lanes per row
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
 
     const int bh = blockIdx.y, chunk = blockIdx.x;
     const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
-    const uint16_t *Xh = X + (size_t)bh * N * D;
+    const uint16_t *Xh = X + (bh / H) * st.b + (bh % H) * st.h;
     const int r0 = chunk * kStatRows;
     const int r1 = min(r0 + kStatRows, N);
 
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0;
     for (int r = r0 + rr; r < r1; r += RP) {
-        const uint4 u = *reinterpret_cast<const uint4 *>(Xh + (size_t)r * D + co * 8);
+        const uint4 u = *reinterpret_cast<const uint4 *>(Xh + r * st.n + co * 8);
         float f[8];
         unpack8<BF16>(u, f);
 #pragma unroll
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(1024) void finalize_vscale_kernel(const float *__re
 // grid (blocks, B*H), 256 threads.
 // ---------------------------------------------------------------------------
 template <bool BF16, int D, int BLOCK, bool SMOOTH>
-__global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X,
+__global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X, Strides st, int H,
                                                          const float *__restrict__ mean,
                                                          int8_t *__restrict__ codes,
                                                          float *__restrict__ scale, int N, int nblk) {
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restr
 
     const int bh = blockIdx.y, blk = blockIdx.x;
     const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
-    const uint16_t *Xh = X + (size_t)bh * N * D;
+    const uint16_t *Xh = X + (bh / H) * st.b + (bh % H) * st.h;
 
     float mu[8];
 #pragma unroll
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restr
     for (int it = 0; it < ITER; ++it) {
         const int r = blk * BLOCK + it * RP + rr;
         if (r < N) {
-            const uint4 u = *reinterpret_cast<const uint4 *>(Xh + (size_t)r * D + co * 8);
+            const uint4 u = *reinterpret_cast<const uint4 *>(Xh + r * st.n + co * 8);
             unpack8<BF16>(u, x[it]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restr
 // D*128-byte burst.  grid (tiles, B*H), 256 threads.
 // ---------------------------------------------------------------------------
 template <bool BF16, int D>
-__global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict__ V,
+__global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict__ V, Strides st, int H,
                                                       const float *__restrict__ v_rcp,
                                                       uint8_t *__restrict__ Vt, int N, int nT) {
     constexpr int LPR = D / 8;
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
     __shared__ uint32_t tile[D * 32];
 
     const int bh = blockIdx.y, T = blockIdx.x;
-    const uint16_t *Vh = V + (size_t)bh * N * D;
+    const uint16_t *Vh = V + (bh / H) * st.b + (bh % H) * st.h;
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
         const int u = threadIdx.x + 256 * k;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
         for (int i = 0; i < 4; ++i) {
             const int r = T * 128 + kq * 4 + i;
             if (r < N) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(Vh + (size_t)r * D + co * 8);
+                const uint4 raw = *reinterpret_cast<const uint4 *>(Vh + r * st.n + co * 8);
                 unpack8<BF16>(raw, y[i]);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) y[i][j] = y[i][j] * rc[j];
@@ -250,32 +251,33 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <bool BF16, int D>
-hipError_t quant_q_impl(const uint16_t *q, int8_t *q_i8, float *q_scale, int BH, int N, hipStream_t stream) {
+hipError_t quant_q_impl(const uint16_t *q, Strides st, int8_t *q_i8, float *q_scale, int BH, int H, int N,
+                        hipStream_t stream) {
     const int nQ = cdiv(N, kBQ);
-    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, nullptr, q_i8, q_scale, N, nQ);
+    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, st, H, nullptr, q_i8, q_scale, N, nQ);
     return hipGetLastError();
 }
 
 template <bool BF16, int D>
-hipError_t quant_k_impl(const uint16_t *k, int8_t *k_i8, float *k_scale, float *k_mean, int BH, int N,
-                        hipStream_t stream, const QuantScratch &ws) {
+hipError_t quant_k_impl(const uint16_t *k, Strides st, int8_t *k_i8, float *k_scale, float *k_mean, int BH, int H,
+                        int N, hipStream_t stream, const QuantScratch &ws) {
     const int chunks = cdiv(N, kStatRows);
     const int nK = cdiv(N, kBK);
-    colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, N, chunks, ws.k_sum_part, nullptr);
+    colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, st, H, N, chunks, ws.k_sum_part, nullptr);
     finalize_mean_kernel<<<BH, 1024, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
     // K right after its statistics pass: its second read can still be served by the last-level cache
-    quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, k_mean, k_i8, k_scale, N, nK);
+    quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, st, H, k_mean, k_i8, k_scale, N, nK);
     return hipGetLastError();
 }
 
 template <bool BF16, int D>
-hipError_t quant_v_impl(const uint16_t *v, uint8_t *v_fp8, float *v_scale, float v_r, int BH, int N,
-                        hipStream_t stream, const QuantScratch &ws) {
+hipError_t quant_v_impl(const uint16_t *v, Strides st, uint8_t *v_fp8, float *v_scale, float v_r, int BH, int H,
+                        int N, hipStream_t stream, const QuantScratch &ws) {
     const int chunks = cdiv(N, kStatRows);
     const int nT = cdiv(N, kW);
-    colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, N, chunks, nullptr, ws.v_max_part);
+    colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, st, H, N, chunks, nullptr, ws.v_max_part);
     finalize_vscale_kernel<<<BH, 1024, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
-    quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, ws.v_rcp, v_fp8, N, nT);
+    quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, st, H, ws.v_rcp, v_fp8, N, nT);
     return hipGetLastError();
 }
 
@@ -297,38 +299,38 @@ QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d) {
     return ws;
 }
 
-hipError_t launch_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int N, int d, bool bf16,
-                          hipStream_t stream) {
+hipError_t launch_quant_q(const void *q, Strides st, int8_t *q_i8, float *q_scale, int B, int H, int N, int d,
+                          bool bf16, hipStream_t stream) {
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const int BH = B * H;
     if (d == 128)
-        return bf16 ? quant_q_impl<true, 128>(q16, q_i8, q_scale, BH, N, stream)
-                    : quant_q_impl<false, 128>(q16, q_i8, q_scale, BH, N, stream);
-    return bf16 ? quant_q_impl<true, 64>(q16, q_i8, q_scale, BH, N, stream)
-                : quant_q_impl<false, 64>(q16, q_i8, q_scale, BH, N, stream);
+        return bf16 ? quant_q_impl<true, 128>(q16, st, q_i8, q_scale, BH, H, N, stream)
+                    : quant_q_impl<false, 128>(q16, st, q_i8, q_scale, BH, H, N, stream);
+    return bf16 ? quant_q_impl<true, 64>(q16, st, q_i8, q_scale, BH, H, N, stream)
+                : quant_q_impl<false, 64>(q16, st, q_i8, q_scale, BH, H, N, stream);
 }
 
-hipError_t launch_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H, int N, int d,
-                          bool bf16, hipStream_t stream, const QuantScratch &ws) {
+hipError_t launch_quant_k(const void *k, Strides st, int8_t *k_i8, float *k_scale, float *k_mean, int B, int H,
+                          int N, int d, bool bf16, hipStream_t stream, const QuantScratch &ws) {
     const uint16_t *k16 = static_cast<const uint16_t *>(k);
     const int BH = B * H;
     if (d == 128)
-        return bf16 ? quant_k_impl<true, 128>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws)
-                    : quant_k_impl<false, 128>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws);
-    return bf16 ? quant_k_impl<true, 64>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws)
-                : quant_k_impl<false, 64>(k16, k_i8, k_scale, k_mean, BH, N, stream, ws);
+        return bf16 ? quant_k_impl<true, 128>(k16, st, k_i8, k_scale, k_mean, BH, H, N, stream, ws)
+                    : quant_k_impl<false, 128>(k16, st, k_i8, k_scale, k_mean, BH, H, N, stream, ws);
+    return bf16 ? quant_k_impl<true, 64>(k16, st, k_i8, k_scale, k_mean, BH, H, N, stream, ws)
+                : quant_k_impl<false, 64>(k16, st, k_i8, k_scale, k_mean, BH, H, N, stream, ws);
 }
 
-hipError_t launch_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
+hipError_t launch_quant_v(const void *v, Strides st, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws) {
     const uint16_t *v16 = static_cast<const uint16_t *>(v);
     const int BH = B * H;
     if (d == 128) {
-        return bf16 ? quant_v_impl<true, 128>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws)
-                    : quant_v_impl<false, 128>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws);
+        return bf16 ? quant_v_impl<true, 128>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
+                    : quant_v_impl<false, 128>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws);
     }
-    return bf16 ? quant_v_impl<true, 64>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws)
-                : quant_v_impl<false, 64>(v16, v_fp8, v_scale, v_r, BH, N, stream, ws);
+    return bf16 ? quant_v_impl<true, 64>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
+                : quant_v_impl<false, 64>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws);
 }
 
 }  // namespace sage

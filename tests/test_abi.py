@@ -68,6 +68,23 @@ def test_argument_checks_return_codes_without_touching_the_gpu():
     assert L.sage_quant_v(p, p, p, 500.0, 1, 1, 16, 64, 0, None, p, 1 << 20) == EINVAL
     assert L.sage_attn_fwd_quantized(p, p, p, p, p, p, p, 1, 1, 16, 64, 0, 0.0, 1000.0, 0, None) == EINVAL
     assert L.sage_attn_fwd_quantized(p, p, None, p, p, p, p, 1, 1, 16, 64, 0, 0.0, 224.0, 0, None) == EINVAL
+    # strided entry: stride rules are checked on the host before anything is enqueued
+    def strided(qs=None, os_=None, B=1, H=2, N=16):
+        qa = (ctypes.c_int64 * 3)(*qs) if qs else None      # (kept alive until the call returns)
+        oa = (ctypes.c_int64 * 3)(*os_) if os_ else None
+        return L.sage_attn_fwd_strided(p, p, p, p, B, H, H, N, N, 64, qa and ctypes.addressof(qa), None, None,
+                                       oa and ctypes.addressof(oa), 0, 0.0, None, 0, p, 16)
+        # (a valid call reaches the workspace check: EWS)
+    assert strided() == EWS
+    assert strided(qs=(2048, 64, 128)) == EWS                  # token-major input
+    assert strided(qs=(0, 0, 64)) == EWS                       # broadcast input
+    assert strided(qs=(2048, 1024, -64)) == EINVAL             # negative stride
+    assert strided(qs=(2048, 1024, 68)) == EINVAL              # rows not 16-byte aligned
+    assert strided(os_=(2048, 64, 128)) == EWS                 # token-major output
+    assert strided(os_=(2048, 1024, 32)) == EINVAL             # output rows overlap
+    assert strided(os_=(2048, 0, 64)) == EINVAL                # output heads overlap
+    assert strided(os_=(1024, 1024, 64), B=2) == EINVAL        # output batches overlap heads
+    assert strided(os_=(0, 1024, 64), B=1) == EWS              # extent-1 dimensions do not matter
     for code in (0, -1, -2, -3, -99):
         assert isinstance(L.sage_strerror(code), bytes) and len(L.sage_strerror(code)) > 0
 
