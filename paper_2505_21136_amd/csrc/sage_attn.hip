@@ -92,10 +92,11 @@ __device__ __forceinline__ float to_f32(uint32_t u) {
 template <bool BF16>
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
     if constexpr (BF16) {
-        uint32_t ua = __builtin_bit_cast(uint32_t, a), ub = __builtin_bit_cast(uint32_t, b);
-        ua = (ua + 0x7fffu + ((ua >> 16) & 1u)) >> 16;
-        ub = (ub + 0x7fffu + ((ub >> 16) & 1u)) >> 16;
-        return ua | (ub << 16);
+        // one v_cvt_pk_bf16_f32 (round to nearest even)
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const f32x2 v = {a, b};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
     } else {
         const uint32_t ua = __builtin_bit_cast(uint16_t, (_Float16)a);
         const uint32_t ub = __builtin_bit_cast(uint16_t, (_Float16)b);
