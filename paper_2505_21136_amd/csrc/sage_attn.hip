@@ -67,10 +67,17 @@ __device__ __forceinline__ void swap16(float &a, float &b) {
 __device__ __forceinline__ void swap32(float &a, float &b) {
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
 }
+// max of two numbers that are known not to be NaN: one v_max_f32 (fmaxf would first canonicalise
+// both operands, which come out of an asm statement, with two more instructions)
+__device__ __forceinline__ float max_no_nan(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
 __device__ __forceinline__ float rowgroup_max(float x) {
     float a = x, b = x;
     swap16(a, b);
-    a = b = fmaxf(a, b);
+    a = b = max_no_nan(a, b);
     swap32(a, b);
     return fmaxf(a, b);
 }
@@ -159,7 +166,7 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
     const float mo0 = mo + kl0, mo1 = mo + kl1;
-    float lsum0 = 0.0f, lsum1 = 0.0f;
+    float lsum0 = 0.0f, lsum1 = 0.0f;  // (tile 0 assigns: "0 + x" would be a real instruction)
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         if constexpr (MASKED) {
@@ -181,9 +188,15 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
                 for (int i = 0; i < 4; ++i) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
             }
         }
-        lsum0 += p[0] + p[1];
-        lsum1 += p[2] + p[3];
-        int w = 0;
+        if (t == 0) {  // tile 0 is never skipped: every step of a wavefront has a visible key in it
+            lsum0 = p[0] + p[1];
+            lsum1 = p[2] + p[3];
+        } else {
+            lsum0 += p[0] + p[1];
+            lsum1 += p[2] + p[3];
+        }
+        int w;  // both halves are overwritten below: an opaque undefined seed saves the v_mov of a zero
+        asm volatile("" : "=v"(w));
         w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
         w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
         pb[t] = w;
