@@ -199,7 +199,7 @@ int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out,
  * token-major [B,N,H,d] layout or slices of a packed QKV projection; nothing is
  * copied, the kernels read and write through the strides.
  *   *_strides  host pointers to three ELEMENT strides {batch, head, token}; NULL means
- *              contiguous [B,H,N,d].  Inputs: every stride >= 0 and a multiple of 8
+ *              contiguous [B,H,N,d].  Inputs: every stride >= 0, <= 2^40 and a multiple of 8
  *              (16-byte aligned rows; 0 broadcasts that dimension).  Output: the same,
  *              and no two rows may overlap.  SAGE_EINVAL otherwise.
  * All other arguments, the workspace and the result (bit-identical to sage_attn_fwd_gqa

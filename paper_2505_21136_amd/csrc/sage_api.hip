@@ -22,14 +22,14 @@ bool gqa_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal) {
 bool dtype_ok(sage_dtype dt) { return dt == SAGE_F16 || dt == SAGE_BF16; }
 
 // Caller-supplied element strides (batch, head, token); NULL selects contiguous [B,H,N,d].
-// Inputs: non-negative multiples of 8 elements (rows stay 16-byte aligned; 0 broadcasts).
+// Inputs: non-negative multiples of 8 elements (rows stay 16-byte aligned; 0 broadcasts), at most 2^40.
 bool read_strides(const int64_t *s, int H, int N, int d, sage::Strides *out) {
     if (!s) {
         *out = sage::contiguous_bhnd(H, N, d);
         return true;
     }
     for (int i = 0; i < 3; ++i)
-        if (s[i] < 0 || s[i] % 8 != 0) return false;
+        if (s[i] < 0 || s[i] % 8 != 0 || s[i] > ((int64_t)1 << 40)) return false;  // (bounded: offsets stay far from 2^63)
     *out = sage::Strides{s[0], s[1], s[2]};
     return true;
 }

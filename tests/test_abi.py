@@ -80,6 +80,7 @@ def test_argument_checks_return_codes_without_touching_the_gpu():
     assert strided(qs=(0, 0, 64)) == EWS                       # broadcast input
     assert strided(qs=(2048, 1024, -64)) == EINVAL             # negative stride
     assert strided(qs=(2048, 1024, 68)) == EINVAL              # rows not 16-byte aligned
+    assert strided(qs=(1 << 41, 1024, 64)) == EINVAL           # beyond the stride bound
     assert strided(os_=(2048, 64, 128)) == EWS                 # token-major output
     assert strided(os_=(2048, 1024, 32)) == EINVAL             # output rows overlap
     assert strided(os_=(2048, 0, 64)) == EINVAL                # output heads overlap
