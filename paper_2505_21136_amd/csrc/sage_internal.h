@@ -10,7 +10,10 @@ namespace sage {
 constexpr int kBQ = 128;        // tokens per Q quantisation block
 constexpr int kBK = 64;         // tokens per K quantisation block
 constexpr int kW = 128;         // keys per online-softmax step (= V tile)
-constexpr int kStatRows = 256;   // tokens per partial column statistic
+#ifndef SAGE_STAT_ROWS
+#define SAGE_STAT_ROWS 256
+#endif
+constexpr int kStatRows = SAGE_STAT_ROWS;  // tokens per partial column statistic
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 

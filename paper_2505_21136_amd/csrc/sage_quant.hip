@@ -60,16 +60,27 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
     acc_t acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0;
-    for (int r = r0 + rr; r < r1; r += RP) {
-        const uint4 u = *reinterpret_cast<const uint4 *>(Xh + r * st.n + co * 8);
-        float f[8];
-        unpack8<BF16>(u, f);
+    // four independent 16-byte loads in flight per thread (one per trip leaves the kernel bound by
+    // memory latency); rows past the end contribute zeros, which change neither a sum nor a max of |.|
+    constexpr int UNROLL = 4;
+    for (int rb = r0 + rr; rb < r1; rb += RP * UNROLL) {
+        uint4 u[UNROLL];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if constexpr (IS_V) {
-                acc[j] = fmaxf(acc[j], fabsf(f[j]));
-            } else {
-                acc[j] += (double)f[j];
+        for (int k = 0; k < UNROLL; ++k) {
+            const int r = rb + k * RP;
+            u[k] = r < r1 ? *reinterpret_cast<const uint4 *>(Xh + r * st.n + co * 8) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            float f[8];
+            unpack8<BF16>(u[k], f);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if constexpr (IS_V) {
+                    acc[j] = fmaxf(acc[j], fabsf(f[j]));
+                } else {
+                    acc[j] += (double)f[j];
+                }
             }
         }
     }
