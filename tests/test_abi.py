@@ -59,6 +59,11 @@ def test_argument_checks_return_codes_without_touching_the_gpu():
     # bad dtype, bad sizes
     assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 7, p, 1 << 20) == EINVAL
     assert L.sage_attn_fwd(p, p, p, p, 1, 1, 0, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    # documented size limits: N <= 2^22, B*H <= 65535 (one more is refused, the limit itself passes the check)
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, (1 << 22) + 1, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    assert L.sage_attn_fwd(p, p, p, p, 1, 1, 1 << 22, 64, 0, 0.0, None, 0, p, 16) == EWS
+    assert L.sage_attn_fwd(p, p, p, p, 256, 256, 16, 64, 0, 0.0, None, 0, p, 1 << 20) == EINVAL
+    assert L.sage_attn_fwd(p, p, p, p, 5, 13107, 16, 64, 0, 0.0, None, 0, p, 16) == EWS
     # workspace too small / missing
     assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, p, 16) == EWS
     assert L.sage_attn_fwd(p, p, p, p, 1, 1, 16, 64, 0, 0.0, None, 0, None, 1 << 20) == EWS
