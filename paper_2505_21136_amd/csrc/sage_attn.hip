@@ -166,7 +166,7 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
     const float mo0 = mo + kl0, mo1 = mo + kl1;
-    float lsum0 = 0.0f, lsum1 = 0.0f;  // (tile 0 assigns: "0 + x" would be a real instruction)
+    float lsum0 = -0.0f, lsum1 = -0.0f;  // x + (-0) is x for every x: the first addition folds away
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         if constexpr (MASKED) {
@@ -188,13 +188,8 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
                 for (int i = 0; i < 4; ++i) p[i] = s[t][i] == INT_MIN ? 0.0f : p[i];
             }
         }
-        if (t == 0) {  // tile 0 is never skipped: every step of a wavefront has a visible key in it
-            lsum0 = p[0] + p[1];
-            lsum1 = p[2] + p[3];
-        } else {
-            lsum0 += p[0] + p[1];
-            lsum1 += p[2] + p[3];
-        }
+        lsum0 += p[0] + p[1];
+        lsum1 += p[2] + p[3];
         int w;  // both halves are overwritten below: an opaque undefined seed saves the v_mov of a zero
         asm volatile("" : "=v"(w));
         w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
@@ -372,14 +367,21 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
                     const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
 #pragma unroll
                     for (int hh = 0; hh < 2; ++hh) {
-                        uint32_t packed = 0u;
+                        // code = rne(fl(x * rcp)): adding 1.5*2^23 to the (separately rounded) product rounds
+                        // it to the nearest integer, ties to even, and leaves the code's two's-complement
+                        // byte in the low byte of the sum's bit pattern; three byte permutes pack four codes
+                        uint32_t b[4];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const uint32_t u = w[2 * hh + (i >> 1)];
                             const float x = to_f32<BF16>((i & 1) ? (u >> 16) : (u & 0xffffu));
-                            packed |= ((uint32_t)(int)__builtin_rintf(x * rcp) & 0xffu) << (8 * i);
+                            float y = x * rcp;
+                            asm volatile("" : "+v"(y));  // keeps the product a rounded binary32 value (no FMA)
+                            b[i] = __builtin_bit_cast(uint32_t, y + kMagicF);
                         }
-                        qreg[qt][ch][2 * h + hh] = (int)packed;
+                        const uint32_t lo2 = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+                        const uint32_t hi2 = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+                        qreg[qt][ch][2 * h + hh] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
                     }
                 }
     } else {
