@@ -31,8 +31,8 @@ PEAK_HBM = 8.0e12            # B/s
 # (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); filled from
 # the summaries under profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/attn_kernel_cfg5_counters.md: 912505 KiB x 2.0 fetched + 251840 KiB x 1.0 written
-    "cfg5": int(912505 * 1024 * 2.0 + 251840 * 1024 * 1.0),
+    # profiles/attn_kernel_cfg5_counters.md: 885116 KiB x 2.0 fetched + 196608 KiB x 1.0 written
+    "cfg5": int(885116 * 1024 * 2.0 + 196608 * 1024 * 1.0),
 }
 
 
