@@ -7,7 +7,7 @@
 // step of 128 keys the K^ tile [128][D] int8 and the V^ tile [D][128] fp8 are
 // copied global -> LDS by buffer loads that write LDS directly (no register
 // staging, out-of-range rows read as zero), double buffered so that the copy of
-// step j+1 runs under the arithmetic of step j with one barrier per step.
+// step j+1 runs under the arithmetic of step j (two barriers per step, see "Schedule").
 // 16-byte LDS chunks are XOR-swizzled against bank conflicts.
 //   S^T = K^ Q^T   with v_mfma_i32_16x16x64_i8 (keys are MFMA rows, queries are
 //                  MFMA columns).  A lane then holds, for ONE query (lane&15),
