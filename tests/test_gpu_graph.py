@@ -1,0 +1,51 @@
+"""The whole forward pass under HIP graph capture: the library only enqueues kernels on the caller's
+stream (no allocation, no memset, no synchronisation), so a captured call must replay to the same
+bits as the eager call, on every replay and with other work between the replays."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_21136_amd as sage
+import workloads as wl
+from gpu_util import say
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("idx,causal", [(2, True), (3, False)])
+def test_captured_forward_replays_bit_exactly(idx, causal):
+    base = wl.CONFIGS[idx - 1]
+    cfg = base.scaled(B=1, H=3, N=700)
+    q, k, v = (t.to(DEV) for t in wl.generate(cfg))
+    q2, k2, v2 = (t.to(DEV) for t in wl.generate(cfg, seed=wl.SEED0 + 77))
+    ws = torch.empty(sage.workspace_bytes(cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.uint8, device=DEV)
+    eager1 = sage.sage_attn_fwd(q, k, v, causal=causal, workspace=ws).clone()
+    eager2 = sage.sage_attn_fwd(q2, k2, v2, causal=causal, workspace=ws).clone()
+    torch.cuda.synchronize()
+
+    # static buffers of the graph
+    gq, gk, gv = q.clone(), k.clone(), v.clone()
+    gout = torch.empty_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sage.sage_attn_fwd(gq, gk, gv, causal=causal, out=gout, workspace=ws)      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sage.sage_attn_fwd(gq, gk, gv, causal=causal, out=gout, workspace=ws)
+    say(f"[graph] captured {cfg.name} causal={causal}")
+
+    for rep, (src, want) in enumerate([((q, k, v), eager1), ((q2, k2, v2), eager2), ((q, k, v), eager1),
+                                       ((q2, k2, v2), eager2)]):
+        gq.copy_(src[0]); gk.copy_(src[1]); gv.copy_(src[2])
+        gout.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(gout.view(torch.int16), want.view(torch.int16)), f"replay {rep} differs from the eager call"
+        # eager work of the program between the replays, sharing the workspace
+        again = sage.sage_attn_fwd(q, k, v, causal=causal, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(again.view(torch.int16), eager1.view(torch.int16))
