@@ -49,3 +49,22 @@ def test_captured_forward_replays_bit_exactly(idx, causal):
         again = sage.sage_attn_fwd(q, k, v, causal=causal, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(again.view(torch.int16), eager1.view(torch.int16))
+
+
+def test_non_finite_inputs_do_not_disturb_the_device():
+    """NaN / Inf inputs are numerically undefined but every address is data-independent: the call
+    completes, and a following call on finite data gives the same bits as before."""
+    cfg = wl.CONFIGS[0].scaled(B=1, H=2, N=300)
+    q, k, v = (t.to(DEV) for t in wl.generate(cfg))
+    want = sage.sage_attn_fwd(q, k, v, causal=True).clone()
+    bad_q, bad_k, bad_v = q.clone(), k.clone(), v.clone()
+    bad_q[0, 0, 5, 3] = float("nan")
+    bad_k[0, 1, 17, :] = float("inf")
+    bad_v[0, 0, 100, 7] = float("-inf")
+    bad_k[0, 0, 200, 9] = 65504.0
+    out = sage.sage_attn_fwd(bad_q, bad_k, bad_v, causal=True)
+    torch.cuda.synchronize()
+    assert out.shape == q.shape
+    again = sage.sage_attn_fwd(q, k, v, causal=True)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), want.view(torch.int16))
