@@ -124,6 +124,16 @@ int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r,
                  int B, int H, int N, int d, sage_dtype dt, void *stream,
                  void *workspace, size_t workspace_bytes);
 
+/*
+ * sage_quant_k and sage_quant_v for K and V of one shape in one call  [same passages]:
+ * the two tensors share their launches (three kernels instead of six); every output
+ * is bit-identical to the separate calls.  Arguments as for those two calls.
+ */
+int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, float *k_mean,
+                  uint8_t *v_fp8, float *v_scale, float v_r,
+                  int B, int H, int N, int d, sage_dtype dt, void *stream,
+                  void *workspace, size_t workspace_bytes);
+
 /* ---- stage 2 ----------------------------------------------------------- */
 
 /*
@@ -173,7 +183,7 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
                                   float sm_scale, float p_r, sage_dtype dt, void *stream);
 
 /*
- * The whole forward pass: sage_quant_k + sage_quant_v + sage_attn_fwd_kvquantized_gqa
+ * The whole forward pass: sage_quant_kv + sage_attn_fwd_kvquantized_gqa
  * with the default ranges (P_r = 224, V_r = 4.5), intermediates in `workspace`
  * (device, >= sage_workspace_bytes(), 256-byte aligned).  The result is bit-identical
  * to sage_quant_qk + sage_quant_v + sage_attn_fwd_quantized.
@@ -185,8 +195,8 @@ int sage_attn_fwd(const void *q, const void *k, const void *v, void *out,
                   sage_dtype dt, void *workspace, size_t workspace_bytes);
 
 /*
- * The whole forward pass for grouped-query / cross attention: sage_quant_k +
- * sage_quant_v + sage_attn_fwd_kvquantized_gqa, default ranges,
+ * The whole forward pass for grouped-query / cross attention: sage_quant_kv +
+ * sage_attn_fwd_kvquantized_gqa, default ranges,
  * workspace >= sage_workspace_bytes_gqa().
  */
 int sage_attn_fwd_gqa(const void *q, const void *k, const void *v, void *out,

@@ -19,7 +19,7 @@ __all__ = [
     "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
-    "sage_attn_fwd_strided", "workspace_bytes_gqa",
+    "sage_attn_fwd_strided", "sage_quant_kv", "workspace_bytes_gqa",
     "v_fp8_to_token_major", "EXPORTS",
 ]
 
@@ -27,7 +27,8 @@ SAGE_F16, SAGE_BF16 = 0, 1
 EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_workspace_bytes",
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
-           "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided"]
+           "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
+           "sage_quant_kv"]
 
 
 class SageError(RuntimeError):
@@ -74,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.sage_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, i, vp, sz]
         L.sage_attn_fwd_strided.restype = i
         L.sage_attn_fwd_strided.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, i, f, vp, i, vp, sz]
+        L.sage_quant_kv.restype = i
+        L.sage_quant_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -180,6 +183,25 @@ def sage_quant_k(k: torch.Tensor, workspace: torch.Tensor | None = None):
     _check(lib().sage_quant_k(k.data_ptr(), k_i8.data_ptr(), k_scale.data_ptr(), k_mean.data_ptr(), B, H, N, d,
                               _dt(k), _stream(), ws.data_ptr(), ws.numel()))
     return k_i8, k_scale, k_mean
+
+
+def sage_quant_kv(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):
+    """K and V of one shape in one call -> (k_i8, k_scale, k_mean, v_fp8, v_scale), as sage_quant_k / sage_quant_v."""
+    _dev(k, v)
+    if k.shape != v.shape or k.dtype != v.dtype:
+        raise SageError("k and v must share shape and dtype")
+    B, H, N, d = k.shape
+    dev = k.device
+    k_i8 = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    k_scale = torch.empty((B, H, -(-N // 64)), dtype=torch.float32, device=dev)
+    k_mean = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    v_fp8 = torch.empty((B, H, -(-N // 128), d, 128), dtype=torch.uint8, device=dev)
+    v_scale = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    ws = workspace if workspace is not None else _workspace(quant_workspace_bytes(B, H, N, d), dev)
+    _check(lib().sage_quant_kv(k.data_ptr(), v.data_ptr(), k_i8.data_ptr(), k_scale.data_ptr(), k_mean.data_ptr(),
+                               v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(k), _stream(),
+                               ws.data_ptr(), ws.numel()))
+    return k_i8, k_scale, k_mean, v_fp8, v_scale
 
 
 def sage_quant_v(v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):

@@ -180,6 +180,22 @@ int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B
                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
 
+int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, float *k_mean, uint8_t *v_fp8,
+                  float *v_scale, float v_r, int B, int H, int N, int d, sage_dtype dt, void *stream, void *workspace,
+                  size_t workspace_bytes) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!k || !v || !k_i8 || !k_scale || !k_mean || !v_fp8 || !v_scale) return SAGE_EINVAL;
+    if (!(v_r > 0.0f) || !(v_r <= 448.0f)) return SAGE_EINVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale))
+        return SAGE_EINVAL;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
+        return SAGE_EWORKSPACE;
+    const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
+    const sage::Strides st = sage::contiguous_bhnd(H, N, d);
+    return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
+                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+}
+
 int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                                 const float *k_scale, const float *v_scale, void *out, int B, int Hq, int Hkv,
                                 int Nq, int Nk, int d, int causal, float sm_scale, float p_r, sage_dtype out_dt,
@@ -237,8 +253,8 @@ int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out
     const sage::QuantScratch qws = sage::quant_scratch_layout(w.quant, B, Hkv, Nk, d);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = dt == SAGE_BF16;
-    hipError_t e = sage::launch_quant_k(k, ks, w.k_i8, w.k_scale, w.k_mean, B, Hkv, Nk, d, bf16, s, qws);
-    if (e == hipSuccess) e = sage::launch_quant_v(v, vs, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk, d, bf16, s, qws);
+    hipError_t e = sage::launch_quant_kv(k, ks, v, vs, w.k_i8, w.k_scale, w.k_mean, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk,
+                                         d, bf16, s, qws);
     // Q is quantised inside the attention kernel: Q^ and delta_Q never touch memory
     if (e == hipSuccess)
         e = sage::launch_attn(q, true, qs, w.k_i8, w.v_fp8, nullptr, w.k_scale, w.v_scale, out, os, B, Hq, Hkv, Nq, Nk, d,

@@ -41,6 +41,11 @@ hipError_t launch_quant_k(const void *k, Strides k_st, int8_t *k_i8, float *k_sc
 hipError_t launch_quant_v(const void *v, Strides v_st, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N,
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
 
+// K and V of the same shape together: three launches instead of six, identical results
+hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v_st, int8_t *k_i8, float *k_scale,
+                           float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
+                           bool bf16, hipStream_t stream, const QuantScratch &ws);
+
 // stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys.
 // q_raw = false: q is Q^ (int8) with scales q_scale; q_raw = true: q is the unquantised 16-bit Q
 // (type of the output), quantised inside the kernel, q_scale unused.  q and out are addressed

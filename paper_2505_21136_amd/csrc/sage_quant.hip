@@ -39,19 +39,23 @@ __device__ __forceinline__ void unpack8(const uint4 &u, float (&f)[8]) {
 // Partial column statistics over chunks of kStatRows tokens.
 //   IS_V = false: sum_n K[n][c] in double (smoothing mean, Sec. 3)
 //   IS_V = true : max_n |V[n][c]|        (per-channel FP8 scale, Sec. 2.1)
-// grid (chunks, B*H), 256 threads; a thread owns 8 adjacent channels.
+// One workgroup of 256 threads per (chunk, batch*head); a thread owns 8 adjacent channels.
+// Launched per tensor (grid (chunks, B*H)) or for K and V together (grid (chunks, B*H, 2)).
 // ---------------------------------------------------------------------------
+template <int D>
+constexpr int colstats_smem_bytes() {
+    return (256 / (D / 8)) * D * (int)sizeof(double);
+}
+
 template <bool BF16, int D, bool IS_V>
-__global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restrict__ X, Strides st, int H, int N,
-                                                       int chunks,
-                                                       double *__restrict__ sum_part,
-                                                       float *__restrict__ max_part) {
+__device__ __forceinline__ void colstats_body(const uint16_t *__restrict__ X, Strides st, int H, int N, int chunks,
+                                              double *__restrict__ sum_part, float *__restrict__ max_part,
+                                              void *smem, int bh, int chunk) {
     constexpr int LPR = D / 8;     // lanes per row
     constexpr int RP = 256 / LPR;  // rows per pass
     using acc_t = typename std::conditional<IS_V, float, double>::type;
-    __shared__ acc_t sm[RP][D];
+    acc_t(*sm)[D] = reinterpret_cast<acc_t(*)[D]>(smem);
 
-    const int bh = blockIdx.y, chunk = blockIdx.x;
     const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
     const uint16_t *Xh = X + (bh / H) * st.b + (bh % H) * st.h;
     const int r0 = chunk * kStatRows;
@@ -105,13 +109,33 @@ __global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restric
     }
 }
 
+template <bool BF16, int D, bool IS_V>
+__global__ __launch_bounds__(256) void colstats_kernel(const uint16_t *__restrict__ X, Strides st, int H, int N,
+                                                       int chunks, double *__restrict__ sum_part,
+                                                       float *__restrict__ max_part) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[colstats_smem_bytes<D>()];
+    colstats_body<BF16, D, IS_V>(X, st, H, N, chunks, sum_part, max_part, smem, blockIdx.y, blockIdx.x);
+}
+
+// K sums (blockIdx.z == 0) and V maxima (blockIdx.z == 1) in one launch
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void colstats_kv_kernel(const uint16_t *__restrict__ K, Strides k_st,
+                                                          const uint16_t *__restrict__ V, Strides v_st, int H, int N,
+                                                          int chunks, double *__restrict__ sum_part,
+                                                          float *__restrict__ max_part) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[colstats_smem_bytes<D>()];
+    if (blockIdx.z == 0)
+        colstats_body<BF16, D, false>(K, k_st, H, N, chunks, sum_part, nullptr, smem, blockIdx.y, blockIdx.x);
+    else
+        colstats_body<BF16, D, true>(V, v_st, H, N, chunks, nullptr, max_part, smem, blockIdx.y, blockIdx.x);
+}
+
 // mean[c] = float(sum / N).  1024 threads: 1024/D threads share a channel, each adds every
 // (1024/D)-th partial sum in chunk order, the shares are added in a fixed order through LDS
 // (the loads of one thread are independent, so the loop is not a chain of memory latencies).
-__global__ __launch_bounds__(1024) void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N,
-                                                             int D, float *__restrict__ mean) {
-    __shared__ double sm[1024];
-    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
+__device__ __forceinline__ void finalize_mean_body(const double *__restrict__ sum_part, int chunks, int N, int D,
+                                                   float *__restrict__ mean, double *sm, int bh) {
+    const int c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
     double s = 0.0;
     for (int i = part; i < chunks; i += parts) s += sum_part[((size_t)bh * chunks + i) * D + c];
     sm[threadIdx.x] = s;
@@ -123,11 +147,10 @@ __global__ __launch_bounds__(1024) void finalize_mean_kernel(const double *__res
 }
 
 // delta_V[c] = a_c / V_r and the multiplier V_r / a_c (0 for an all-zero channel); same thread layout.
-__global__ __launch_bounds__(1024) void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D,
-                                                               float v_r, float *__restrict__ v_scale,
-                                                               float *__restrict__ v_rcp) {
-    __shared__ float sm[1024];
-    const int bh = blockIdx.x, c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
+__device__ __forceinline__ void finalize_vscale_body(const float *__restrict__ max_part, int chunks, int D, float v_r,
+                                                     float *__restrict__ v_scale, float *__restrict__ v_rcp,
+                                                     float *sm, int bh) {
+    const int c = threadIdx.x % D, part = threadIdx.x / D, parts = 1024 / D;
     float a = 0.0f;
     for (int i = part; i < chunks; i += parts) a = fmaxf(a, max_part[((size_t)bh * chunks + i) * D + c]);
     sm[threadIdx.x] = a;
@@ -139,23 +162,46 @@ __global__ __launch_bounds__(1024) void finalize_vscale_kernel(const float *__re
     }
 }
 
+__global__ __launch_bounds__(1024) void finalize_mean_kernel(const double *__restrict__ sum_part, int chunks, int N,
+                                                             int D, float *__restrict__ mean) {
+    __shared__ double sm[1024];
+    finalize_mean_body(sum_part, chunks, N, D, mean, sm, blockIdx.x);
+}
+
+__global__ __launch_bounds__(1024) void finalize_vscale_kernel(const float *__restrict__ max_part, int chunks, int D,
+                                                               float v_r, float *__restrict__ v_scale,
+                                                               float *__restrict__ v_rcp) {
+    __shared__ float sm[1024];
+    finalize_vscale_body(max_part, chunks, D, v_r, v_scale, v_rcp, sm, blockIdx.x);
+}
+
+// the K mean (blockIdx.y == 0) and the V scales (blockIdx.y == 1) in one launch
+__global__ __launch_bounds__(1024) void finalize_kv_kernel(const double *__restrict__ sum_part,
+                                                           const float *__restrict__ max_part, int chunks, int N, int D,
+                                                           float v_r, float *__restrict__ mean,
+                                                           float *__restrict__ v_scale, float *__restrict__ v_rcp) {
+    __shared__ double sm[1024];
+    if (blockIdx.y == 0)
+        finalize_mean_body(sum_part, chunks, N, D, mean, sm, blockIdx.x);
+    else
+        finalize_vscale_body(max_part, chunks, D, v_r, v_scale, v_rcp, reinterpret_cast<float *>(sm), blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------
 // Per-block INT8 quantisation (Sec. 2.1): one workgroup per block of BLOCK
 // tokens, the block lives in registers between the max pass and the code pass.
-// grid (blocks, B*H), 256 threads.
+// 256 threads; wmax: four floats of LDS.
 // ---------------------------------------------------------------------------
 template <bool BF16, int D, int BLOCK, bool SMOOTH>
-__global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X, Strides st, int H,
-                                                         const float *__restrict__ mean,
-                                                         int8_t *__restrict__ codes,
-                                                         float *__restrict__ scale, int N, int nblk) {
+__device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, Strides st, int H,
+                                                const float *__restrict__ mean, int8_t *__restrict__ codes,
+                                                float *__restrict__ scale, int N, int nblk, float *wmax, int bh,
+                                                int blk) {
     constexpr int LPR = D / 8;
     constexpr int RP = 256 / LPR;
     constexpr int ITER = BLOCK / RP;
     static_assert(BLOCK % RP == 0, "block must be a multiple of the rows covered per pass");
-    __shared__ float wmax[4];
 
-    const int bh = blockIdx.y, blk = blockIdx.x;
     const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
     const uint16_t *Xh = X + (bh / H) * st.b + (bh % H) * st.h;
 
@@ -210,17 +256,15 @@ __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restr
 // 64*(t>>2) + 16*g + 4*(t&3) + i of a row = key 16*t + 4*g + i of the tile.  A thread converts
 // 4 consecutive keys x 8 channels, so the four keys of one channel pack into
 // one dword; the tile is transposed through LDS and leaves as one contiguous
-// D*128-byte burst.  grid (tiles, B*H), 256 threads.
+// D*128-byte burst.  256 threads; tile: D*32 dwords of LDS.
 // ---------------------------------------------------------------------------
 template <bool BF16, int D>
-__global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict__ V, Strides st, int H,
-                                                      const float *__restrict__ v_rcp,
-                                                      uint8_t *__restrict__ Vt, int N, int nT) {
+__device__ __forceinline__ void quant_v_body(const uint16_t *__restrict__ V, Strides st, int H,
+                                             const float *__restrict__ v_rcp, uint8_t *__restrict__ Vt, int N, int nT,
+                                             uint32_t *tile, int bh, int T) {
     constexpr int LPR = D / 8;
     constexpr int UPT = 32 * LPR / 256;  // (key quad, channel octet) units per thread
-    __shared__ uint32_t tile[D * 32];
 
-    const int bh = blockIdx.y, T = blockIdx.x;
     const uint16_t *Vh = V + (bh / H) * st.b + (bh % H) * st.h;
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
@@ -259,6 +303,41 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
     for (int k = 0; k < D / 32; ++k) dst[threadIdx.x + 256 * k] = src[threadIdx.x + 256 * k];
 }
 
+// grid (blocks, B*H)
+template <bool BF16, int D, int BLOCK, bool SMOOTH>
+__global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X, Strides st, int H,
+                                                         const float *__restrict__ mean, int8_t *__restrict__ codes,
+                                                         float *__restrict__ scale, int N, int nblk) {
+    __shared__ float wmax[4];
+    quant_int8_body<BF16, D, BLOCK, SMOOTH>(X, st, H, mean, codes, scale, N, nblk, wmax, blockIdx.y, blockIdx.x);
+}
+
+// grid (tiles, B*H)
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict__ V, Strides st, int H,
+                                                      const float *__restrict__ v_rcp, uint8_t *__restrict__ Vt, int N,
+                                                      int nT) {
+    __shared__ uint32_t tile[D * 32];
+    quant_v_body<BF16, D>(V, st, H, v_rcp, Vt, N, nT, tile, blockIdx.y, blockIdx.x);
+}
+
+// K blocks (blockIdx.x < nK) and V tiles (the rest) in one launch: grid (nK + nT, B*H)
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restrict__ K, Strides k_st,
+                                                       const float *__restrict__ mean, int8_t *__restrict__ k_codes,
+                                                       float *__restrict__ k_scale, int nK,
+                                                       const uint16_t *__restrict__ V, Strides v_st,
+                                                       const float *__restrict__ v_rcp, uint8_t *__restrict__ Vt, int nT,
+                                                       int H, int N) {
+    __shared__ uint32_t tile[D * 32];
+    const int x = blockIdx.x;  // (workgroup-uniform branch)
+    if (x < nK)
+        quant_int8_body<BF16, D, kBK, true>(K, k_st, H, mean, k_codes, k_scale, N, nK, reinterpret_cast<float *>(tile),
+                                            blockIdx.y, x);
+    else
+        quant_v_body<BF16, D>(V, v_st, H, v_rcp, Vt, N, nT, tile, blockIdx.y, x - nK);
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <bool BF16, int D>
@@ -289,6 +368,22 @@ hipError_t quant_v_impl(const uint16_t *v, Strides st, uint8_t *v_fp8, float *v_
     colstats_kernel<BF16, D, true><<<dim3(chunks, BH), 256, 0, stream>>>(v, st, H, N, chunks, nullptr, ws.v_max_part);
     finalize_vscale_kernel<<<BH, 1024, 0, stream>>>(ws.v_max_part, chunks, D, v_r, v_scale, ws.v_rcp);
     quant_v_kernel<BF16, D><<<dim3(nT, BH), 256, 0, stream>>>(v, st, H, ws.v_rcp, v_fp8, N, nT);
+    return hipGetLastError();
+}
+
+// K and V of one shape in three launches instead of six (same kernels' bodies, same results)
+template <bool BF16, int D>
+hipError_t quant_kv_impl(const uint16_t *k, Strides k_st, const uint16_t *v, Strides v_st, int8_t *k_i8, float *k_scale,
+                         float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int BH, int H, int N,
+                         hipStream_t stream, const QuantScratch &ws) {
+    const int chunks = cdiv(N, kStatRows);
+    const int nK = cdiv(N, kBK), nT = cdiv(N, kW);
+    colstats_kv_kernel<BF16, D><<<dim3(chunks, BH, 2), 256, 0, stream>>>(k, k_st, v, v_st, H, N, chunks, ws.k_sum_part,
+                                                                         ws.v_max_part);
+    finalize_kv_kernel<<<dim3(BH, 2), 1024, 0, stream>>>(ws.k_sum_part, ws.v_max_part, chunks, N, D, v_r, k_mean,
+                                                         v_scale, ws.v_rcp);
+    quant_kv_kernel<BF16, D><<<dim3(nK + nT, BH), 256, 0, stream>>>(k, k_st, k_mean, k_i8, k_scale, nK, v, v_st, ws.v_rcp,
+                                                                    v_fp8, nT, H, N);
     return hipGetLastError();
 }
 
@@ -342,6 +437,18 @@ hipError_t launch_quant_v(const void *v, Strides st, uint8_t *v_fp8, float *v_sc
     }
     return bf16 ? quant_v_impl<true, 64>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
                 : quant_v_impl<false, 64>(v16, st, v_fp8, v_scale, v_r, BH, H, N, stream, ws);
+}
+
+hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v_st, int8_t *k_i8, float *k_scale,
+                           float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
+                           bool bf16, hipStream_t stream, const QuantScratch &ws) {
+    const uint16_t *k16 = static_cast<const uint16_t *>(k), *v16 = static_cast<const uint16_t *>(v);
+    const int BH = B * H;
+#define SAGE_KV(BF, DD) \
+    quant_kv_impl<BF, DD>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
+    if (d == 128) return bf16 ? SAGE_KV(true, 128) : SAGE_KV(false, 128);
+    return bf16 ? SAGE_KV(true, 64) : SAGE_KV(false, 64);
+#undef SAGE_KV
 }
 
 }  // namespace sage

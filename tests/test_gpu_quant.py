@@ -77,3 +77,22 @@ def test_degenerate_inputs():
 @pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_quant_full_size_configs(idx):
     _run(wl.CONFIGS[idx - 1])
+
+
+@pytest.mark.parametrize("idx,shape", [(1, (1, 2, 1024, 128)), (2, (2, 3, 777, 128)), (3, (1, 4, 1, 64)),
+                                       (4, (1, 2, 4500, 64)), (5, (1, 2, 2049, 128))])
+def test_joint_kv_quantiser_equals_the_separate_calls(idx, shape):
+    """sage_quant_kv shares the launches of K and V; every output must be the same bits."""
+    base = wl.CONFIGS[idx - 1]
+    B, H, N, d = shape
+    cfg = wl.Workload("kv", base.index, B, H, N, d, False, base.dtype, base.q_dist, base.k_outlier_channels)
+    _, k, v = wl.generate(cfg)
+    k, v = k.to("cuda:0"), v.to("cuda:0")
+    k_i8, k_scale, k_mean = sage.sage_quant_k(k)
+    v_fp8, v_scale = sage.sage_quant_v(v, 4.5)
+    joint = sage.sage_quant_kv(k, v, 4.5)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("k_i8", "k_scale", "k_mean", "v_fp8", "v_scale"), (k_i8, k_scale, k_mean, v_fp8, v_scale),
+                          joint):
+        assert a.shape == b.shape and a.dtype == b.dtype, name
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
