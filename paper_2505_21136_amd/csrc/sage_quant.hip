@@ -66,7 +66,10 @@ __device__ __forceinline__ void colstats_body(const uint16_t *__restrict__ X, St
     for (int j = 0; j < 8; ++j) acc[j] = 0;
     // four independent 16-byte loads in flight per thread (one per trip leaves the kernel bound by
     // memory latency); rows past the end contribute zeros, which change neither a sum nor a max of |.|
-    constexpr int UNROLL = 4;
+#ifndef SAGE_STAT_UNROLL
+#define SAGE_STAT_UNROLL 4
+#endif
+    constexpr int UNROLL = SAGE_STAT_UNROLL;
     for (int rb = r0 + rr; rb < r1; rb += RP * UNROLL) {
         uint4 u[UNROLL];
 #pragma unroll
