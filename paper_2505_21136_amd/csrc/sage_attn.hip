@@ -232,7 +232,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const void *__restrict__ Qsrc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
     uint16_t *__restrict__ out, Strides q_st, Strides o_st, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq,
-    int group, float sm_scale, float log2_pr) {
+    int group, float sm_scale, float log2_pr, int nQtiles) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
     constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
     constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
@@ -250,11 +250,38 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = wave >= NWAVE / 2 ? 1 : 0;  // second group runs one slot behind
     const int lq = lane & 15, g = lane >> 4;
-    // non-causal: grid (query tile, head) -- co-resident workgroups share a head's K^/V^ tiles in L2;
-    // causal: grid (head, query tile), longest rows first over ALL heads, so that the short
-    // workgroups fill the tail of the launch (greedy longest-first balances the CUs)
-    const int bh = CAUSAL ? (int)blockIdx.x : (int)blockIdx.y;  // (batch, query head)
-    const int qtile = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.x;
+    // Workgroup -> (head, query tile); the grid is one-dimensional.  The hardware deals consecutive
+    // workgroup ids round-robin to the 8 XCDs, each with an L2 of its own: workgroup id is the `slot`-th
+    // of XCD `xcd`.  Co-resident workgroups of an XCD should stream through the same K^/V^ tiles (its L2
+    // then serves every fetch after the first), and a causal launch must also end on its short tiles.
+    const int n_items = (int)gridDim.x, n_qt = nQtiles, n_bh = n_items / n_qt;
+    const int xcd = (int)blockIdx.x % 8, slot = (int)blockIdx.x / 8;
+    int bh, qtile;  // (batch, query head), query tile
+    if (!CAUSAL && n_qt >= 128) {
+        // a head has 16 or more tiles per XCD anyway: ids in order (query tile fastest), every XCD works
+        // on the same one or two heads, and a tile missed by one L2 is likely still in the last-level cache
+        bh = (int)blockIdx.x / n_qt;
+        qtile = (int)blockIdx.x % n_qt;
+    } else if (!CAUSAL) {
+        // shorter sequences: head-major items cut into 8 contiguous ranges, one per XCD, walked in order
+        // (otherwise an XCD would hold only n_qt/8 tiles of each of many heads at a time)
+        const int pos = xcd * (n_items / 8) + min(xcd, n_items % 8) + slot;
+        bh = pos / n_qt;
+        qtile = pos % n_qt;
+    } else if (n_bh % 8 == 0) {
+        // an XCD owns n_bh/8 adjacent heads and takes them in windows of G heads -- enough tiles to fill
+        // its 64 workgroup slots twice --, inside a window the longest tiles of all heads first
+        const int hp = n_bh / 8;
+        const int G = max(1, min(hp, (127 + n_qt) / n_qt));
+        const int w = slot / (G * n_qt), r = slot - w * G * n_qt;
+        const int hw = min(G, hp - w * G);  // heads in this window (the last one may be short)
+        bh = xcd * hp + w * G + r % hw;
+        qtile = n_qt - 1 - r / hw;
+    } else {
+        // any other head count: longest tiles first over all heads
+        bh = (int)blockIdx.x % n_bh;
+        qtile = n_qt - 1 - (int)blockIdx.x / n_bh;
+    }
     const int wg_row0 = qtile * BM;
     const int row0 = wg_row0 + wave * (16 * NQ);
     // grouped-query attention: `group` consecutive query heads share one K/V head
@@ -523,14 +550,14 @@ hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8,
                     int Nk, bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
     constexpr int BM = 16 * NQ * NWAVE;
     const int BH = B * Hq;
-    const dim3 grid = causal ? dim3(BH, cdiv(Nq, BM)) : dim3(cdiv(Nq, BM), BH);
+    const dim3 grid(BH * cdiv(Nq, BM));  // (at most 65535 * 32768 < 2^31 workgroups)
     const int nT = cdiv(Nk, kW), nQ = cdiv(Nq, kBQ), nK = cdiv(Nk, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
 #define SAGE_LAUNCH(C, BF, QR)                                                                              \
     attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR><<<grid, NWAVE * 64, 0, stream>>>(q, k_i8, v_fp8, q_scale, k_scale, \
                                                                              v_scale, o16, q_st, o_st, Nq, Nk,  \
                                                                              nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
-                                                                             log2_pr)
+                                                                             log2_pr, cdiv(Nq, BM))
 #define SAGE_LAUNCH_Q(C, BF) \
     if (q_raw) SAGE_LAUNCH(C, BF, true); else SAGE_LAUNCH(C, BF, false)
     if (causal) {
