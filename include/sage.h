@@ -7,7 +7,8 @@
  * NULL = the default stream).  Inputs are never modified.
  *
  * Tensors.  Q, K, V and the output are contiguous [B, H, N, d] arrays of a
- * 16-bit floating type (`sage_dtype`), d in {64, 128}, N >= 1 arbitrary.  The
+ * 16-bit floating type (`sage_dtype`), d in {64, 128}, 1 <= N <= 2^22 arbitrary
+ * (not a multiple of anything), B*H <= 65535; larger sizes return SAGE_EINVAL.  The
  * plain entry points take N_q = N_k = N and H_q = H_kv = H; the *_gqa entry
  * points take Q/out as [B, Hq, Nq, d] and K/V as [B, Hkv, Nk, d], Hq a multiple
  * of Hkv (query head h uses K/V head h / (Hq/Hkv)).
@@ -49,7 +50,7 @@ typedef enum { SAGE_F16 = 0, SAGE_BF16 = 1 } sage_dtype;
 
 enum {
     SAGE_OK = 0,
-    SAGE_EINVAL = -1,     /* NULL pointer, d not in {64,128}, sizes < 1, pointer not 16-byte aligned */
+    SAGE_EINVAL = -1,     /* NULL pointer, d not in {64,128}, size out of range, pointer not 16-byte aligned */
     SAGE_EWORKSPACE = -2, /* workspace missing or smaller than the matching *_workspace_bytes() */
     SAGE_EHIP = -3        /* a kernel launch failed; text from sage_strerror() */
 };
