@@ -244,6 +244,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     __shared__ __attribute__((aligned(1024))) uint8_t ldsK[2][TILE];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsV[2][TILE];
     __shared__ float q_wave_max[NWAVE];
+    __shared__ __attribute__((aligned(16))) float dv_lds[D];  // delta_V of this head, for the epilogue
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -374,6 +375,9 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         pb[qt] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
+    // the output scales are fetched now and parked in LDS: the epilogue then waits for no global load
+    if (tid < D / 4)
+        *reinterpret_cast<float4 *>(dv_lds + 4 * tid) = *reinterpret_cast<const float4 *>(dv + (size_t)bhk * D + 4 * tid);
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): K^(0) has landed
     __syncthreads();
 
@@ -534,7 +538,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 const int c = 16 * ct + 4 * g;
-                const float4 sc = *reinterpret_cast<const float4 *>(dv + (size_t)bhk * D + c);
+                const float4 sc = *reinterpret_cast<const float4 *>(dv_lds + c);
                 const float y0 = o[ct][qt][0] * (sc.x * inv), y1 = o[ct][qt][1] * (sc.y * inv);
                 const float y2 = o[ct][qt][2] * (sc.z * inv), y3 = o[ct][qt][3] * (sc.w * inv);
                 *reinterpret_cast<uint2 *>(orow + c) = make_uint2(pack2<BF16>(y0, y1), pack2<BF16>(y2, y3));
