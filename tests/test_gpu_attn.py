@@ -137,3 +137,34 @@ def test_attn_full_size_configs(idx):
     assert_parity(ref, got, f"{cfg.name} sampled {ref.shape[0]} rows")
     # reported, not gated (parity unpinned): accuracy against full-precision attention
     say(f"   vs full precision: cos={wl.cos_sim(fp, got):.6f} relL1={wl.rel_l1(fp, got):.4f} rmse={wl.rmse(fp, got):.4e}")
+
+
+@pytest.mark.parametrize("B,H,N,causal", [
+    (1, 24, 8200, True),     # 3 heads per XCD in windows of 2: a short last window
+    (1, 40, 4100, True),     # 5 heads per XCD in windows of 4 + 1
+    (1, 9, 3000, True),      # head count not a multiple of 8: longest-first over all heads
+    (1, 3, 16500, False),    # 129 tiles per head: in-order map
+    (1, 5, 2000, False),     # 80 tiles, not a multiple of 8: uneven contiguous ranges
+])
+def test_launch_map_covers_every_tile(B, H, N, causal):
+    """Shapes that reach every branch of the workgroup -> (head, query tile) map: every output row must
+    be written (the output starts as NaN), and sampled rows must match the oracle."""
+    cfg = wl.Workload("map", 3, B, H, N, 64, causal, "bf16")
+    say(f"[attn] launch map B{B} H{H} N{N} causal={causal}")
+    q, k, v = wl.generate(cfg, seed=wl.SEED0 + 500 + H)
+    sm = np.float32(cfg.sm_scale)
+    out = torch.full(q.shape, float("nan"), dtype=q.dtype, device=DEV)
+    sage.sage_attn_fwd(q.to(DEV), k.to(DEV), v.to(DEV), causal=causal, sm_scale=float(sm), out=out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    refs, gots = [], []
+    for h in sorted({0, H // 2, H - 1}):
+        qf, kf, vf = (wl.as_f32(t[0, h]) for t in (q, k, v))
+        quant = oracle.quantize_head(qf, kf, vf)
+        for r0 in (0, (N // 2) // 128 * 128, (N - 1) // 128 * 128):
+            r1 = min(N, r0 + 128)
+            ref, _ = oracle.sage_attention_head(qf, kf, vf, causal=causal, sm_scale=sm, out_dtype="bf16", row0=r0,
+                                                row1=r1, quant=quant)
+            refs.append(ref)
+            gots.append(out[0, h, r0:r1].float().cpu().numpy())
+    assert_parity(np.concatenate(refs), np.concatenate(gots), "launch map")
