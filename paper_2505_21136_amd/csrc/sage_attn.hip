@@ -202,17 +202,17 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
 }
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Enqueue the global -> LDS copy of one [128 x D]-byte tile (K^ or V^) of key step j.  Every buffer
-// load moves 16 bytes per lane straight into LDS at dst + 1024*(k*NWAVE + wave) + 16*lane; the
-// per-lane source offsets carry the swizzle, the tile offset rides in the scalar offset.
-template <int D, int NWAVE, int CPY>
-__device__ __forceinline__ void issue_tile_copy(uint8_t *dst, __amdgpu_buffer_rsrc_t rsrc, const int (&voff)[CPY],
-                                                int wave, int j) {
+// Enqueue piece k of the global -> LDS copy of one [128 x D]-byte tile (K^ or V^) of key step j.  A tile is
+// copied by the NW wavefronts of one group, CPG pieces each; a piece (one buffer load) moves 16 bytes per
+// lane straight into LDS at dst + 1024*(k*NW + w) + 16*lane; the per-lane source offset carries the
+// swizzle, the tile offset rides in the scalar offset.
+template <int D, int NW>
+__device__ __forceinline__ void issue_tile_piece(uint8_t *dst, __amdgpu_buffer_rsrc_t rsrc, int voff, int w, int k,
+                                                 int j) {
     constexpr int TILE = 128 * D;
-#pragma unroll
-    for (int k = 0; k < CPY; ++k)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + (k * NWAVE + wave) * 1024), 16, voff[k],
-                                                 j * TILE, 0, 0);
+    // (piece k of a wavefront lies NW KB after piece 0 on both sides: the swizzles repeat every 8 rows)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + (k * NW + w) * 1024), 16, voff,
+                                             j * TILE + k * NW * 1024, 0, 0);
 }
 #endif  // __HIP_DEVICE_COMPILE__
 
@@ -220,8 +220,9 @@ __device__ __forceinline__ void issue_tile_copy(uint8_t *dst, __amdgpu_buffer_rs
 // same per-step sequence  M(j) = [PV(j-1), QK(j)]  ->  S(j) = softmax(j)  one slot apart: while
 // one group is in its matrix slot (MFMA + LDS reads) the other is in its softmax slot (vector
 // ALU), so the two pipes of every SIMD are busy at the same time instead of colliding.  A slot
-// ends with a workgroup barrier.  Tile copies for K^(j+1) and V^(j) are issued at the start of
-// slot 2j and are needed from slot 2j+2 on: two slots of latency to hide them.
+// ends with a workgroup barrier.  The copy of K^(j+1) is issued by the first group at the start of
+// slot 2j, the copy of V^(j) by the second group at the start of slot 2j+1 (each in its own matrix
+// slot); both are needed from slot 2j+2 on.
 //
 // QRAW: Q arrives unquantised (16-bit, the output's type) and the workgroup, whose 128 rows are
 // exactly one Q quantisation block, quantises it in its prologue (paper Sec. 2.1: per-block INT8,
@@ -239,8 +240,9 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     constexpr int CT = D / 16;           // 16-channel tiles of the output
     constexpr int TILE = 128 * D;        // bytes of one K^ (or V^) tile
     constexpr int NTHR = NWAVE * 64;
-    constexpr int CPY = TILE / 16 / NTHR;  // 16-byte chunks each thread copies per tile
-    static_assert(TILE / 16 % NTHR == 0, "tile chunks must divide over the threads");
+    constexpr int NWG = NWAVE / 2;                 // wavefronts per group
+    constexpr int CPG = TILE / 16 / (NTHR / 2);    // 16-byte chunks a thread copies per tile (one group copies a tile)
+    static_assert(TILE / 16 % (NTHR / 2) == 0, "tile chunks must divide over the threads of a group");
     __shared__ __attribute__((aligned(1024))) uint8_t ldsK[2][TILE];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsV[2][TILE];
     __shared__ float q_wave_max[NWAVE];
@@ -296,19 +298,23 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kh, 0, Nk * D, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vh, 0, nT * D * 128, 0x00020000);
 
-    // per-lane source offsets of the tile copies (the LDS side is linear in the lane index)
-    int k_voff[CPY], v_voff[CPY];
-#pragma unroll
-    for (int k = 0; k < CPY; ++k) {
-        const int slot = (k * NWAVE + wave) * 64 + lane;
-        {
+    // Tile copies.  The first group copies the K^ tiles, the second the V^ tiles, each at the start of its own
+    // matrix slot: the texture path accepts one 1 KB piece per 16 cycles per CU, and a wavefront that cannot
+    // issue its piece cannot issue anything else either -- harmless in the matrix slot (it has slack), costly
+    // in front of the softmax arithmetic (which is the critical path).
+    // Per-lane source offset of this wavefront's piece 0 (the LDS side is linear in the lane index):
+    const int wig = wave % NWG;  // wavefront within its group
+    int c_voff;
+    {
+        static_assert(NWG * 64 % (8 * (D / 16)) == 0 && NWG * 8 % 8 == 0, "pieces must be whole swizzle periods apart");
+        const int slot = wig * 64 + lane;
+        if (grp == 0) {
             constexpr int CPR = D / 16;  // chunks per K row
             const int row = slot / CPR, pc = slot % CPR;
-            k_voff[k] = row * D + ((pc ^ k_swz<D>(row)) << 4);
-        }
-        {
+            c_voff = row * D + ((pc ^ k_swz<D>(row)) << 4);
+        } else {
             const int row = slot >> 3, pc = slot & 7;
-            v_voff[k] = row * 128 + ((pc ^ (row & 7)) << 4);
+            c_voff = row * 128 + ((pc ^ (row & 7)) << 4);
         }
     }
 
@@ -317,7 +323,10 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // steps this wavefront takes part in (causal: tiles entirely above its rows are skipped)
     int my_steps = nsteps;
     if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
-    issue_tile_copy<D, NWAVE, CPY>(ldsK[0], k_rsrc, k_voff, wave, 0);
+    if (grp == 0) {
+#pragma unroll
+        for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], k_rsrc, c_voff, wig, k, 0);
+    }
 
     // the lane's B operand of S^T = K^ Q^T: 16 consecutive channels (64*ch + 16*g ..) of query row lq
     v4i qreg[NQ][KC];
@@ -420,10 +429,18 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     }
     const double cq = (double)delta_q * (double)sm_scale * 1.4426950408889634;
 
-    // start of an even slot 2*jj: fetch K^(jj+1) and V^(jj)
-    auto issue_copies = [&](int jj) {
-        if (jj + 1 < nsteps) issue_tile_copy<D, NWAVE, CPY>(ldsK[(jj + 1) & 1], k_rsrc, k_voff, wave, jj + 1);
-        if (jj < nsteps) issue_tile_copy<D, NWAVE, CPY>(ldsV[jj & 1], v_rsrc, v_voff, wave, jj);
+    // piece k of the copy this group makes during its matrix slot M(j): K^(j+1) (first group), V^(j) (second)
+    auto copy_k = [&](int j) {
+        if (j + 1 < nsteps) {
+#pragma unroll
+            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[(j + 1) & 1], k_rsrc, c_voff, wig, k, j + 1);
+        }
+    };
+    auto copy_v = [&](int j) {
+        if (j < nsteps) {
+#pragma unroll
+            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsV[j & 1], v_rsrc, c_voff, wig, k, j);
+        }
     };
     // matrix slot M(j): PV(j-1), then QK(j)
     auto matrix_slot = [&](int j) {
@@ -502,11 +519,13 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         }
     };
 
-    // 2*nsteps + 2 slots, one barrier each; copies issued at even slots are awaited at the end of
-    // the following odd slot
+    // 2*nsteps + 2 slots, one barrier each.  K^(j+1) is copied during slot 2j (the first group's M(j)) and
+    // V^(j) during slot 2j+1 (the second group's M(j)); both are first read in slot 2j+2 and both target
+    // buffers whose last readers finished in slot 2j-1.  Every wavefront waits for its own pieces before the
+    // barrier that ends slot 2j+1.
     if (grp == 0) {
         for (int j = 0; j <= nsteps; ++j) {
-            issue_copies(j);  // slot 2j
+            copy_k(j);  // slot 2j
             matrix_slot(j);
             __syncthreads();
             softmax_slot(j);  // slot 2j+1
@@ -514,15 +533,14 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             __syncthreads();
         }
     } else {
-        issue_copies(0);  // slot 0: this group idles
-        __syncthreads();
+        __syncthreads();  // slot 0: this group idles
         for (int j = 0; j <= nsteps; ++j) {
-            matrix_slot(j);  // slot 2j+1
+            copy_v(j);  // slot 2j+1
+            matrix_slot(j);
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
             __syncthreads();
             if (j < nsteps) {
-                issue_copies(j + 1);  // slot 2j+2
-                softmax_slot(j);
+                softmax_slot(j);  // slot 2j+2
                 __syncthreads();
             }
         }
