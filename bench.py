@@ -53,8 +53,8 @@ def main():
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path shards over batch*heads with no "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path would shard over batch*heads with no "
+              "exchange between the GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
