@@ -487,6 +487,9 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // softmax slot S(j)
     auto softmax_slot = [&](int j) {
         if (j >= my_steps) return;
+        // the softmax part is the critical path of a slot (the matrix part has slack): its wavefront goes
+        // first when both want the vector issue port
+        __builtin_amdgcn_s_setprio(1);
         const int key0 = j * kW;
         // de-quantisation constants of the two K blocks of this step
         if ((j & 31) == 0) {
@@ -517,6 +520,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
                                                 8);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     // 2*nsteps + 2 slots, one barrier each.  K^(j+1) is copied during slot 2j (the first group's M(j)) and
