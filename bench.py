@@ -40,7 +40,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps before the timed ones (default: at least 3 and at least 0.15 s of them -- "
+                         "the clock of a GPU coming out of idle takes some tens of ms of load to settle)")
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the d=128, N=32768 target workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
@@ -113,8 +115,18 @@ def main():
         calib = torch.empty_like(q)
         calib.copy_(q)
         torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        step()
+    if args.warmup is None:
+        t_w = time.perf_counter()
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        more = int(0.15 / max((time.perf_counter() - t_w) / 3, 1e-5))
+        for _ in range(more):  # enqueued back to back, like the timed steps
+            step()
+        args.warmup = 3 + more
+    else:
+        for _ in range(args.warmup):
+            step()
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
