@@ -1,4 +1,4 @@
-"""Seeded sweep over random small shapes: batch, head grouping, N_q, N_k, head dimension, dtype, mask and
+"""Seeded sweep over random shapes (1 to 2600 keys): batch, head grouping, N_q, N_k, head dimension, dtype, mask and
 memory layout are drawn independently, every case goes through the strided entry point and is compared
 with the oracle on the whole output."""
 import numpy as np
@@ -20,8 +20,8 @@ def _cases(n, seed):
     for i in range(n):
         d = int(rng.choice([64, 128]))
         hkv = int(rng.integers(1, 4))
-        group = int(rng.choice([1, 1, 2, 4]))
-        nk = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 700)]))
+        group = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        nk = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 700), rng.integers(700, 2600)]))
         nq = nk if rng.random() < 0.5 else int(rng.integers(1, nk + 1))
         if rng.random() < 0.15:
             nq = int(rng.integers(nk, nk + 200))          # more queries than keys: non-causal only
@@ -31,7 +31,7 @@ def _cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("i,B,Hq,Hkv,Nq,Nk,d,idx,causal,layout", _cases(40, 20250521))
+@pytest.mark.parametrize("i,B,Hq,Hkv,Nq,Nk,d,idx,causal,layout", _cases(60, 20250521))
 def test_random_shape(i, B, Hq, Hkv, Nq, Nk, d, idx, causal, layout):
     base = wl.CONFIGS[idx - 1]
     say(f"[random] #{i} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} {base.dtype} causal={causal} {layout}")
