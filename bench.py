@@ -172,7 +172,7 @@ def main():
             "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
             "kernel_ms": round(attn_ms, 4),
             # what holds the kernel below the MFMA roofline (rocprofv3 counters, profiles/attn_kernel_cfg5_counters.md)
-            "limiter": "vector-ALU issue port (softmax arithmetic shares it with MFMA issue): 86 % busy, MFMA pipe 39 %",
+            "limiter": "vector-ALU issue port (softmax arithmetic shares it with MFMA issue): 91 % busy, MFMA pipe 41 %",
         },
         "quant_stage": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_gbs, 1) if quant_gbs else None,
                         "frac_of_hbm_peak": round(quant_gbs * 1e9 / PEAK_HBM, 4) if quant_gbs else None},
