@@ -323,6 +323,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // steps this wavefront takes part in (causal: tiles entirely above its rows are skipped)
     int my_steps = nsteps;
     if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
+    if (row0 >= Nq) my_steps = 0;  // a wavefront without a valid row only takes part in the copies and barriers
     if (grp == 0) {
 #pragma unroll
         for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], k_rsrc, c_voff, wig, k, 0);
