@@ -117,3 +117,31 @@ def test_v_layout_helper_is_a_permutation():
     assert rows.shape == (1, 1, 200, d)
     want = (torch.arange(200) % 251).to(torch.uint8)[:, None].expand(200, d)
     assert torch.equal(rows[0, 0], want)
+
+
+def test_product_path_and_oracle_are_independent():
+    """Neither side imports, includes or names the other (only tests, smoke() and the CPU leg of bench.py use both)."""
+    pkg = os.path.join(ROOT, "paper_2505_21136_amd")
+    orc = os.path.join(ROOT, "oracle")
+
+    def sources(top):
+        for d, _, files in os.walk(top):
+            if "_build" in d or "__pycache__" in d:
+                continue
+            for f in files:
+                if f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                    yield os.path.join(d, f)
+
+    for path in list(sources(pkg)) + [os.path.join(ROOT, "include", "sage.h")]:
+        assert "oracle" not in open(path).read().lower(), path
+    for path in sources(orc):
+        text = open(path).read()
+        for word in ("paper_2505_21136_amd", "libsage.so", "hip_runtime", "hipcc", "sage_internal", "sage.h"):
+            assert word not in text, (path, word)
+
+
+def test_missing_library_raises(monkeypatch):
+    monkeypatch.setattr(sage, "_lib", None)
+    monkeypatch.setattr(sage._build, "LIB", os.path.join(ROOT, "paper_2505_21136_amd", "no_such_libsage.so"))
+    with pytest.raises(sage.SageError):
+        sage.lib()
