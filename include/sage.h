@@ -2,9 +2,12 @@
  * libsage -- SageAttention2++ "8+8" quantised attention forward for AMD MI355X (gfx950).
  *
  * C ABI.  Every pointer named "device" is a device (HBM) pointer owned by the
- * caller; the library allocates nothing, keeps no state, never synchronises
- * and enqueues all its work on `stream` (a hipStream_t passed as void*;
- * NULL = the default stream).  Inputs are never modified.
+ * caller; the library allocates nothing, never synchronises and enqueues all
+ * its work on `stream` (a hipStream_t passed as void*; NULL = the default
+ * stream).  Inputs are never modified.  The only state it keeps is, per
+ * calling thread, the HIP error code behind the last SAGE_EHIP (read by
+ * sage_strerror); a call that enqueues kernels discards a HIP error left
+ * pending on the thread by earlier, unrelated HIP calls.
  *
  * Tensors.  Q, K, V and the output are contiguous [B, H, N, d] arrays of a
  * 16-bit floating type (`sage_dtype`), d in {64, 128}, 1 <= N <= 2^22 arbitrary
@@ -143,7 +146,8 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
  *   out      device, [B,H,N,d] of `out_dt`; every element is written     (out)
  *   causal   0: all keys visible; 1: key n visible to query r iff n <= r;
  *            key tiles entirely above the diagonal are skipped
- *   sm_scale softmax scale; <= 0 or NaN selects 1/sqrt(d)
+ *   sm_scale softmax scale; anything but a positive finite number (0, negative,
+ *            NaN, infinity) selects 1/sqrt(d)
  *   p_r      FP8 range of P~ (224 by default), must lie in (0, 448]
  * The running maximum is updated once per SAGE_W keys to the exact step
  * maximum; l accumulates the unquantised P~.

@@ -1,6 +1,9 @@
 // C ABI of libsage (declared in include/sage.h): argument checks, workspace
 // carving and kernel launches.  No allocation, no synchronisation; the only
 // state is the last HIP error code of the calling thread (for sage_strerror).
+// A call that enqueues kernels first discards whatever error an earlier,
+// unrelated HIP call of this thread left pending, so that SAGE_EHIP always
+// speaks of this call's own launches.
 #include "../../include/sage.h"
 #include "sage_internal.h"
 
@@ -57,6 +60,12 @@ int from_hip(hipError_t e) {
     if (e == hipSuccess) return SAGE_OK;
     g_last_hip_error = e;
     return SAGE_EHIP;
+}
+// Called after the argument checks, right before the first launch of an entry point.
+void discard_pending_hip_error() { (void)hipGetLastError(); }
+// sm_scale as given when it is a positive finite number, 1/sqrt(d) otherwise (0, negative, NaN, infinity)
+float scale_or_default(float sm_scale, int d) {
+    return (isfinite(sm_scale) && sm_scale > 0.0f) ? sm_scale : 1.0f / sqrtf((float)d);
 }
 
 // Carving of the sage_attn_fwd workspace.
@@ -139,6 +148,7 @@ int sage_quant_q(const void *q, int8_t *q_i8, float *q_scale, int B, int H, int 
                  void *stream) {
     if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
     if (!q || !q_i8 || !q_scale || !aligned16(q) || !aligned16(q_i8)) return SAGE_EINVAL;
+    discard_pending_hip_error();
     return from_hip(sage::launch_quant_q(q, sage::contiguous_bhnd(H, N, d), q_i8, q_scale, B, H, N, d, dt == SAGE_BF16,
                                          static_cast<hipStream_t>(stream)));
 }
@@ -150,6 +160,7 @@ int sage_quant_k(const void *k, int8_t *k_i8, float *k_scale, float *k_mean, int
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
         return SAGE_EWORKSPACE;
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
+    discard_pending_hip_error();
     return from_hip(sage::launch_quant_k(k, sage::contiguous_bhnd(H, N, d), k_i8, k_scale, k_mean, B, H, N, d,
                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
@@ -176,6 +187,7 @@ int sage_quant_v(const void *v, uint8_t *v_fp8, float *v_scale, float v_r, int B
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
         return SAGE_EWORKSPACE;
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
+    discard_pending_hip_error();
     return from_hip(sage::launch_quant_v(v, sage::contiguous_bhnd(H, N, d), v_fp8, v_scale, v_r, B, H, N, d,
                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
@@ -192,6 +204,7 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
         return SAGE_EWORKSPACE;
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
     const sage::Strides st = sage::contiguous_bhnd(H, N, d);
+    discard_pending_hip_error();
     return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
                                           dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
@@ -205,8 +218,9 @@ int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const ui
     if (!aligned16(q_i8) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
-    if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
+    sm_scale = scale_or_default(sm_scale, d);
     const sage::Strides st = sage::contiguous_bhnd(Hq, Nq, d);
+    discard_pending_hip_error();
     return from_hip(sage::launch_attn(q_i8, false, st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, st, B, Hq, Hkv, Nq,
                                       Nk, d, causal != 0, sm_scale, p_r, out_dt == SAGE_BF16,
                                       static_cast<hipStream_t>(stream)));
@@ -220,8 +234,9 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
     if (!aligned16(q) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
-    if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
+    sm_scale = scale_or_default(sm_scale, d);
     const sage::Strides st = sage::contiguous_bhnd(Hq, Nq, d);
+    discard_pending_hip_error();
     return from_hip(sage::launch_attn(q, true, st, k_i8, v_fp8, nullptr, k_scale, v_scale, out, st, B, Hq, Hkv, Nq, Nk,
                                       d, causal != 0, sm_scale, p_r, dt == SAGE_BF16,
                                       static_cast<hipStream_t>(stream)));
@@ -248,11 +263,12 @@ int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out
     if (!write_strides_ok(os, B, Hq, Nq, d)) return SAGE_EINVAL;
     if (!workspace || !aligned256(workspace) || workspace_bytes < sage_workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d))
         return SAGE_EWORKSPACE;
-    if (!(sm_scale > 0.0f)) sm_scale = 1.0f / sqrtf((float)d);  // also catches NaN
+    sm_scale = scale_or_default(sm_scale, d);
     const FwdWorkspace w = fwd_layout(workspace, B, Hq, Hkv, Nq, Nk, d);
     const sage::QuantScratch qws = sage::quant_scratch_layout(w.quant, B, Hkv, Nk, d);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = dt == SAGE_BF16;
+    discard_pending_hip_error();
     hipError_t e = sage::launch_quant_kv(k, ks, v, vs, w.k_i8, w.k_scale, w.k_mean, w.v_fp8, w.v_scale, 4.5f, B, Hkv, Nk,
                                          d, bf16, s, qws);
     // Q is quantised inside the attention kernel: Q^ and delta_Q never touch memory

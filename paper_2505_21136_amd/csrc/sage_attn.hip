@@ -6,7 +6,7 @@
 // rows of one (batch, head); a wavefront owns NQ tiles of 16 query rows.  Per
 // step of 128 keys the K^ tile [128][D] int8 and the V^ tile [D][128] fp8 are
 // copied global -> LDS by buffer loads that write LDS directly (no register
-// staging, out-of-range rows read as zero), double buffered so that the copy of
+// staging; chunks beyond the end of a head's K^ are not fetched and read as zero), double buffered so that the copy of
 // step j+1 runs under the arithmetic of step j (two barriers per step, see "Schedule").
 // 16-byte LDS chunks are XOR-swizzled against bank conflicts.
 //   S^T = K^ Q^T   with v_mfma_i32_16x16x64_i8 (keys are MFMA rows, queries are
@@ -205,14 +205,19 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
 // Enqueue piece k of the global -> LDS copy of one [128 x D]-byte tile (K^ or V^) of key step j.  A tile is
 // copied by the NW wavefronts of one group, CPG pieces each; a piece (one buffer load) moves 16 bytes per
 // lane straight into LDS at dst + 1024*(k*NW + w) + 16*lane; the per-lane source offset carries the
-// swizzle, the tile offset rides in the scalar offset.
+// swizzle.  Every piece gets a buffer descriptor of its own whose base is the piece's first byte and whose
+// size is what is left of the head's buffer from there (scalar arithmetic only): the hardware bounds check
+// covers the per-lane offset but not a scalar offset, and this way a 16-byte chunk beyond the last byte of
+// the buffer (rows >= Nk of the last K^ tile) is never fetched and reads as zero.
 template <int D, int NW>
-__device__ __forceinline__ void issue_tile_piece(uint8_t *dst, __amdgpu_buffer_rsrc_t rsrc, int voff, int w, int k,
-                                                 int j) {
+__device__ __forceinline__ void issue_tile_piece(uint8_t *dst, const uint8_t *head, int head_bytes, int voff, int w,
+                                                 int k, int j) {
     constexpr int TILE = 128 * D;
     // (piece k of a wavefront lies NW KB after piece 0 on both sides: the swizzles repeat every 8 rows)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + (k * NW + w) * 1024), 16, voff,
-                                             j * TILE + k * NW * 1024, 0, 0);
+    const int first = j * TILE + k * NW * 1024;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(head + first), 0, max(head_bytes - first, 0), 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + (k * NW + w) * 1024), 16, voff, 0, 0, 0);
 }
 #endif  // __HIP_DEVICE_COMPILE__
 
@@ -292,11 +297,10 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     // causal mask aligned to the end of both sequences: key n visible to query r iff n <= r + shift
     const int shift = Nk - Nq;
 
-    const int8_t *Kh = Kc + (size_t)bhk * Nk * D;
+    // this head's K^ [Nk][D] and V^ [nT][D][128] and their sizes in bytes (the tile copies are bounded to them)
+    const uint8_t *Kh = reinterpret_cast<const uint8_t *>(Kc) + (size_t)bhk * Nk * D;
     const uint8_t *Vh = Vt + (size_t)bhk * nT * D * 128;
-    // buffer descriptors bounded to this head: rows >= Nk of K^ read as zero
-    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kh, 0, Nk * D, 0x00020000);
-    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vh, 0, nT * D * 128, 0x00020000);
+    const int k_bytes = Nk * D, v_bytes = nT * D * 128;
 
     // Tile copies.  The first group copies the K^ tiles, the second the V^ tiles, each at the start of its own
     // matrix slot: the texture path accepts one 1 KB piece per 16 cycles per CU, and a wavefront that cannot
@@ -326,7 +330,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     if (row0 >= Nq) my_steps = 0;  // a wavefront without a valid row only takes part in the copies and barriers
     if (grp == 0) {
 #pragma unroll
-        for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], k_rsrc, c_voff, wig, k, 0);
+        for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], Kh, k_bytes, c_voff, wig, k, 0);
     }
 
     // the lane's B operand of S^T = K^ Q^T: 16 consecutive channels (64*ch + 16*g ..) of query row lq
@@ -434,13 +438,13 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     auto copy_k = [&](int j) {
         if (j + 1 < nsteps) {
 #pragma unroll
-            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[(j + 1) & 1], k_rsrc, c_voff, wig, k, j + 1);
+            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[(j + 1) & 1], Kh, k_bytes, c_voff, wig, k, j + 1);
         }
     };
     auto copy_v = [&](int j) {
         if (j < nsteps) {
 #pragma unroll
-            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsV[j & 1], v_rsrc, c_voff, wig, k, j);
+            for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsV[j & 1], Vh, v_bytes, c_voff, wig, k, j);
         }
     };
     // matrix slot M(j): PV(j-1), then QK(j)

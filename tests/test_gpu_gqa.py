@@ -45,7 +45,7 @@ def test_gqa_and_rectangular(idx, d, causal, B, Hq, Hkv, Nq, Nk):
     assert np.isfinite(got).all()
     ref = oracle.sage_attention(wl.as_f32(q), wl.as_f32(k), wl.as_f32(v), causal=causal, sm_scale=sm,
                                 out_dtype=base.dtype)
-    assert_parity(ref, got, "gqa")
+    assert_parity(ref, got, base.dtype, "gqa")
 
 
 def test_gqa_equals_repeated_kv_heads():

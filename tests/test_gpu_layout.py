@@ -84,4 +84,4 @@ def test_token_major_against_oracle():
     torch.cuda.synchronize()
     ref = oracle.sage_attention(wl.as_f32(q.cpu()), wl.as_f32(k.cpu()), wl.as_f32(v.cpu()), causal=True, sm_scale=sm,
                                 out_dtype=base.dtype)
-    assert_parity(ref, got.transpose(1, 2).float().cpu().numpy(), "bnhd")
+    assert_parity(ref, got.transpose(1, 2).float().cpu().numpy(), base.dtype, "bnhd")

@@ -38,7 +38,7 @@ def test_longest_sequence():
         refs.append(ref)
         gots.append(out[0, 0, r0:r1].float().cpu().numpy())
         say(f"   oracle rows {r0}:{r1} done")
-    assert_parity(np.concatenate(refs), np.concatenate(gots), "N = 2^22")
+    assert_parity(np.concatenate(refs), np.concatenate(gots), "fp16", "N = 2^22")
 
 
 def test_most_heads():
@@ -57,6 +57,6 @@ def test_most_heads():
                                             out_dtype="bf16")
         refs.append(ref)
         gots.append(out[b, h].float().cpu().numpy())
-    assert_parity(np.concatenate(refs), np.concatenate(gots), "B*H = 65535")
+    assert_parity(np.concatenate(refs), np.concatenate(gots), "bf16", "B*H = 65535")
     # one more head is refused
     assert sage.lib().sage_workspace_bytes(5, 13108, N, d) == 0

@@ -81,7 +81,7 @@ def test_fused_q_against_oracle():
     torch.cuda.synchronize()
     ref = oracle.sage_attention(wl.as_f32(q.cpu()), wl.as_f32(k.cpu()), wl.as_f32(v.cpu()), causal=True, sm_scale=sm,
                                 out_dtype=base.dtype)
-    assert_parity(ref, out.float().cpu().numpy(), "qfused")
+    assert_parity(ref, out.float().cpu().numpy(), base.dtype, "qfused")
 
 
 def test_fused_q_argument_checks():

@@ -48,4 +48,4 @@ def test_random_shape(i, B, Hq, Hkv, Nq, Nk, d, idx, causal, layout):
     assert np.isfinite(got).all()
     ref = oracle.sage_attention(wl.as_f32(q), wl.as_f32(k), wl.as_f32(v), causal=causal, sm_scale=sm,
                                 out_dtype=base.dtype)
-    assert_parity(ref, got, f"random #{i}")
+    assert_parity(ref, got, base.dtype, f"random #{i}")

@@ -41,7 +41,7 @@ def test_table2_analogue(idx):
         got = out[0, :, rows].float().cpu().numpy()
         ref = np.stack([oracle_rows(want_q, 0, h, rows.start, rows.stop, causal=False, sm_scale=sm,
                                     out_dtype=cfg.dtype, p_r=p_r) for h in range(cfg.H)])
-        assert_parity(ref, got, f"P_r={p_r:g} V_r={v_r:g} vs oracle")
+        assert_parity(ref, got, cfg.dtype, f"P_r={p_r:g} V_r={v_r:g} vs oracle")
         cos, l1, rm = wl.cos_sim(full, got), wl.rel_l1(full, got), wl.rmse(full, got)
         say(f"   P_r={p_r:<5g} V_r={v_r:<5g} cos={100 * cos:.3f}%  relL1={l1:.5f}  rmse={rm:.3e}")
         l1s.append(l1)
