@@ -48,6 +48,7 @@ extern "C" {
 #define SAGE_BK 64       /* tokens per K quantisation block  */
 #define SAGE_W 128       /* keys consumed per online-softmax step */
 #define SAGE_VTILE 128   /* keys per tile of the transposed FP8 V layout */
+#define SAGE_STATIC_SCRATCH_BYTES (8u << 20) /* scratch built into the library for sage_quant_kv_static */
 
 typedef enum { SAGE_F16 = 0, SAGE_BF16 = 1 } sage_dtype;
 
@@ -55,7 +56,8 @@ enum {
     SAGE_OK = 0,
     SAGE_EINVAL = -1,     /* NULL pointer, d not in {64,128}, size out of range, pointer not 16-byte aligned */
     SAGE_EWORKSPACE = -2, /* workspace missing or smaller than the matching *_workspace_bytes() */
-    SAGE_EHIP = -3        /* a kernel launch failed; text from sage_strerror() */
+    SAGE_EHIP = -3,       /* a kernel launch failed; text from sage_strerror() */
+    SAGE_ESCRATCH = -4    /* sage_quant_kv_static: the problem needs more than SAGE_STATIC_SCRATCH_BYTES */
 };
 
 typedef struct {
@@ -137,6 +139,25 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
                   uint8_t *v_fp8, float *v_scale, float v_r,
                   int B, int H, int N, int d, sage_dtype dt, void *stream,
                   void *workspace, size_t workspace_bytes);
+
+/*
+ * sage_quant_kv for callers that cannot allocate and have no workspace to hand over: code recorded
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * outputs bit for bit; the scratch (partial column statistics, about 12 bytes per channel and 256 tokens
+ * of every head) lives in a static device array inside the library, SAGE_STATIC_SCRATCH_BYTES (8 MiB)
+ * per GPU, which each GPU the library runs on holds until the process ends.  The call allocates nothing
+ * and frees nothing; on its first use on a device it looks up that device's copy of the array (the
+ * device must be current, as for every call).  Arguments as for sage_quant_kv, without the workspace.
+ *   returns SAGE_ESCRATCH when sage_quant_workspace_bytes(B,H,N,d) > SAGE_STATIC_SCRATCH_BYTES
+ *           (nothing is enqueued; use sage_quant_kv), otherwise as sage_quant_kv.
+ * All calls on one GPU share that GPU's array: the scratch keeps the last call's contents (nothing in it
+ * has to start at zero, every value read is written earlier in the same call), and two calls that
+ * overlap on one GPU -- different streams, or different threads -- race on it.  Calls on one stream,
+ * and calls on different GPUs, are safe.
+ */
+int sage_quant_kv_static(const void *k, const void *v, int8_t *k_i8, float *k_scale, float *k_mean,
+                         uint8_t *v_fp8, float *v_scale, float v_r,
+                         int B, int H, int N, int d, sage_dtype dt, void *stream);
 
 /* ---- stage 2 ----------------------------------------------------------- */
 

@@ -19,7 +19,7 @@ __all__ = [
     "SageError", "lib", "get_params", "v_fp8_bytes", "quant_workspace_bytes", "workspace_bytes",
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
-    "sage_attn_fwd_strided", "sage_quant_kv", "workspace_bytes_gqa",
+    "sage_attn_fwd_strided", "sage_quant_kv", "sage_quant_kv_static", "workspace_bytes_gqa",
     "v_fp8_to_token_major", "EXPORTS",
 ]
 
@@ -28,7 +28,7 @@ EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_w
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
            "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
-           "sage_quant_kv"]
+           "sage_quant_kv", "sage_quant_kv_static"]
 
 
 class SageError(RuntimeError):
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.sage_attn_fwd_strided.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, i, f, vp, i, vp, sz]
         L.sage_quant_kv.restype = i
         L.sage_quant_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp, vp, sz]
+        L.sage_quant_kv_static.restype = i
+        L.sage_quant_kv_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -202,6 +204,28 @@ def sage_quant_kv(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace:
                                v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(k), _stream(),
                                ws.data_ptr(), ws.numel()))
     return k_i8, k_scale, k_mean, v_fp8, v_scale
+
+
+def sage_quant_kv_static(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, out=None):
+    """sage_quant_kv through the entry point that uses the library's built-in scratch (no workspace, nothing
+    allocated by the call itself).  `out` = (k_i8, k_scale, k_mean, v_fp8, v_scale) preallocated, or None."""
+    _dev(k, v)
+    if k.shape != v.shape or k.dtype != v.dtype:
+        raise SageError("k and v must share shape and dtype")
+    B, H, N, d = k.shape
+    dev = k.device
+    if out is None:
+        out = (torch.empty((B, H, N, d), dtype=torch.int8, device=dev),
+               torch.empty((B, H, -(-N // 64)), dtype=torch.float32, device=dev),
+               torch.empty((B, H, d), dtype=torch.float32, device=dev),
+               torch.empty((B, H, -(-N // 128), d, 128), dtype=torch.uint8, device=dev),
+               torch.empty((B, H, d), dtype=torch.float32, device=dev))
+    k_i8, k_scale, k_mean, v_fp8, v_scale = out
+    _dev(*out)
+    _check(lib().sage_quant_kv_static(k.data_ptr(), v.data_ptr(), k_i8.data_ptr(), k_scale.data_ptr(),
+                                      k_mean.data_ptr(), v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d,
+                                      _dt(k), _stream()))
+    return out
 
 
 def sage_quant_v(v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):

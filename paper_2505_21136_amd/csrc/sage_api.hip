@@ -9,9 +9,38 @@
 
 #include <math.h>
 
+#include <mutex>
+
 namespace {
 
 thread_local hipError_t g_last_hip_error = hipSuccess;
+
+// Scratch of sage_quant_kv_static: device memory that belongs to the library's code object, one copy per
+// GPU, alive until the process ends.  In host code the array's NAME is only a handle for
+// hipGetSymbolAddress; the address kernels can use is looked up once per device and kept in
+// g_scratch_ptr, and only that pointer is ever handed to a launch.
+static __device__ __align__(256) unsigned char scratch[SAGE_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch` (NULL + error code on failure).  Allocates nothing.
+hipError_t static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -123,6 +152,9 @@ const char *sage_strerror(int code) {
                    "range, Hq not a multiple of Hkv, causal with Nk < Nq)";
         case SAGE_EWORKSPACE: return "workspace missing, misaligned or too small";
         case SAGE_EHIP: return hipGetErrorString(g_last_hip_error);
+        case SAGE_ESCRATCH:
+            return "problem too large for the library's static scratch (sage_quant_workspace_bytes() exceeds "
+                   "SAGE_STATIC_SCRATCH_BYTES): use sage_quant_kv with a caller-supplied workspace";
         default: return "unknown error code";
     }
 }
@@ -205,6 +237,26 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
     const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
     const sage::Strides st = sage::contiguous_bhnd(H, N, d);
     discard_pending_hip_error();
+    return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
+                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+}
+
+int sage_quant_kv_static(const void *k, const void *v, int8_t *k_i8, float *k_scale, float *k_mean, uint8_t *v_fp8,
+                         float *v_scale, float v_r, int B, int H, int N, int d, sage_dtype dt, void *stream) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!k || !v || !k_i8 || !k_scale || !k_mean || !v_fp8 || !v_scale) return SAGE_EINVAL;
+    if (!(v_r > 0.0f) || !(v_r <= 448.0f)) return SAGE_EINVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale))
+        return SAGE_EINVAL;
+    if (sage_quant_workspace_bytes(B, H, N, d) > (size_t)SAGE_STATIC_SCRATCH_BYTES) return SAGE_ESCRATCH;
+    discard_pending_hip_error();
+    void *ptr = nullptr;
+    const hipError_t e = static_scratch(&ptr);
+    if (e != hipSuccess) return from_hip(e);
+    // every partial statistic and every reciprocal the code pass reads is written by the statistics pass of the
+    // same call, so nothing in the scratch has to start at zero
+    const sage::QuantScratch ws = sage::quant_scratch_layout(ptr, B, H, N, d);
+    const sage::Strides st = sage::contiguous_bhnd(H, N, d);
     return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
                                           dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
 }
