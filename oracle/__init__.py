@@ -60,6 +60,9 @@ def _load():
         lib.sage_oracle_attn_rows.restype = None
         lib.sage_oracle_attn_rows.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
                                               c_i, c_i, c_i, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_attn_rows_blockmax.restype = None
+        lib.sage_oracle_attn_rows_blockmax.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
+                                                       c_i, c_i, c_i, c_i, c_i, c_i, vp]
         lib.sage_oracle_attn_rows_fp.restype = None
         lib.sage_oracle_attn_rows_fp.argtypes = [vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_i, c_i, c_i, vp, vp]
         lib.sage_oracle_num_threads.restype = c_i
@@ -153,8 +156,11 @@ def quant_v(V: np.ndarray, v_r: float = V_R):
 # --------------------------------------------------------------------------
 def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: float = P_R,
               bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
-              out_dtype="bf16", want_p: bool = False):
-    """Quantised attention of query rows [row0, row1): Q^ is [Nq, d], K^ and V^ are [Nk, d]."""
+              out_dtype="bf16", want_p: bool = False, delta_p: str = "static"):
+    """Quantised attention of query rows [row0, row1): Q^ is [Nq, d], K^ and V^ are [Nk, d].
+
+    delta_p = "static" (the method as built: delta_P = 1/P_r) or "block_max" (Section 3.1 Eq. 2 read literally:
+    delta_P = max(P~)/P_r per (Q block x key step); a study mode, CPU only)."""
     Qc, Kc = _c(Qc, np.int8), _c(Kc, np.int8)
     Vc = _c(Vc, np.uint8)
     dq, dk, dv = _c(dq, np.float32), _c(dk, np.float32), _c(dv, np.float32)
@@ -168,6 +174,12 @@ def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: flo
     assert 0 <= row0 <= row1 <= Nq
     code = {"fp16": 0, "bf16": 1, None: -1}[out_dtype]
     out = np.empty((row1 - row0, d), dtype=np.float64)
+    if delta_p == "block_max":
+        assert not want_p
+        _load().sage_oracle_attn_rows_blockmax(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
+                                               float(sm_scale), float(p_r), bq, bk, w, row0, row1, code, _p(out))
+        return out
+    assert delta_p == "static", delta_p
     P = np.empty((row1 - row0, Nk), dtype=np.float64) if want_p else None
     _load().sage_oracle_attn_rows(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
                                   float(sm_scale), float(p_r), bq, bk, w, row0, row1, code,
@@ -203,13 +215,13 @@ def quantize_head(q, k, v, *, v_r: float = V_R, bq: int = BQ, bk: int = BK):
 
 def sage_attention_head(q, k, v, *, causal: bool, sm_scale: float, out_dtype: str,
                         p_r: float = P_R, v_r: float = V_R, bq: int = BQ, bk: int = BK, w: int = W,
-                        row0: int = 0, row1=None, quant=None):
+                        row0: int = 0, row1=None, quant=None, delta_p: str = "static"):
     """Whole path for one head; returns (output rows as float64, quantised operands)."""
     if quant is None:
         quant = quantize_head(q, k, v, v_r=v_r, bq=bq, bk=bk)
     out = attn_rows(quant["q_codes"], quant["k_codes"], quant["v_codes"], quant["q_scale"],
                     quant["k_scale"], quant["v_scale"], causal=causal, sm_scale=sm_scale, p_r=p_r,
-                    bq=bq, bk=bk, w=w, row0=row0, row1=row1, out_dtype=out_dtype)
+                    bq=bq, bk=bk, w=w, row0=row0, row1=row1, out_dtype=out_dtype, delta_p=delta_p)
     return out, quant
 
 

@@ -309,6 +309,116 @@ void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc
     free(Vd);
 }
 
+/* Study variant of sage_oracle_attn_rows: Section 3.1, Eq. (2) read literally.  There the scale of P~ is
+ * taken per block, delta_P = max(P~) / P_r, a block of P~ being one Q block (BQ rows) times one key step
+ * (W keys); the routine above uses the constant delta_P = 1 / P_r instead (P~ <= 1 by construction, and a
+ * block's maximum IS 1 whenever one of its rows finds its running maximum in that step).  Here, per
+ * Q block and key step,
+ *     b     = max over the block's rows and visible keys of P~      (0 < b <= 1; b = 0: nothing visible)
+ *     P^_n  = e4m3(P~_n * P_r / b)                                  i.e. P~ / delta_P with delta_P = b / P_r
+ *     acc   = alpha*acc + b * sum_n P^_n * V^[n][:]                 i.e. P^ V^ * delta_P, P_r divided out at the end
+ * everything else as above (m, alpha, l per row; l from the unquantised P~).  The block maximum couples the
+ * rows of a Q block, so whole Q blocks are evaluated even if only rows [row0, row1) are returned.
+ * This mode exists to measure what the static scale costs or gains; the GPU library does not implement it. */
+void sage_oracle_attn_rows_blockmax(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc,
+                                    const float *dq, const float *dk, const float *dv,
+                                    int Nq, int Nk, int d, int causal, double sm_scale, double p_r,
+                                    int BQ, int BK, int W, int row0, int row1, int out_dtype, double *out)
+{
+    const int N = Nk;
+    const int shift = Nk - Nq;
+    double *Vd = (double *)malloc((size_t)N * d * sizeof(double));
+    for (size_t i = 0; i < (size_t)N * d; ++i)
+        Vd[i] = sage_oracle_e4m3_decode(Vc[i]);
+    int blk0 = row0 / BQ, blk1 = (row1 + BQ - 1) / BQ;
+
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)BQ * W * sizeof(double));   /* scores, then P~, of one block */
+        double *acc = (double *)malloc((size_t)BQ * d * sizeof(double));
+        double *m = (double *)malloc((size_t)BQ * sizeof(double));
+        double *l = (double *)malloc((size_t)BQ * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int i = blk0; i < blk1; ++i) {
+            int r0 = i * BQ;
+            int r1 = r0 + BQ < Nq ? r0 + BQ : Nq;
+            int rows = r1 - r0;
+            for (int a = 0; a < rows; ++a) {
+                m[a] = -INFINITY;
+                l[a] = 0.0;
+                for (int c = 0; c < d; ++c)
+                    acc[(size_t)a * d + c] = 0.0;
+            }
+            int last = causal ? (r1 - 1) + shift : N - 1;  /* last key any row of the block sees */
+            for (int t0 = 0; t0 <= last; t0 += W) {
+                int t1 = t0 + W < N ? t0 + W : N;
+                double b = 0.0;
+                for (int a = 0; a < rows; ++a) {
+                    int r = r0 + a;
+                    const int8_t *qr = Qc + (size_t)r * d;
+                    double *xa = x + (size_t)a * W;
+                    double mx = -INFINITY;
+                    for (int n = t0; n < t1; ++n) {
+                        if (causal && n > r + shift) {
+                            xa[n - t0] = -INFINITY;
+                            continue;
+                        }
+                        const int8_t *kn = Kc + (size_t)n * d;
+                        int32_t s = 0;
+                        for (int c = 0; c < d; ++c)
+                            s += (int32_t)qr[c] * (int32_t)kn[c];
+                        double cst = (double)dq[r / BQ] * (double)dk[n / BK] * sm_scale * SAGE_ORACLE_LOG2E;
+                        xa[n - t0] = (double)s * cst;
+                        if (xa[n - t0] > mx)
+                            mx = xa[n - t0];
+                    }
+                    double m_new = m[a] > mx ? m[a] : mx;
+                    /* a row with nothing visible yet keeps m = -inf: alpha is irrelevant (l = acc = 0) */
+                    double alpha = isinf(m_new) ? 1.0 : exp2(m[a] - m_new);
+                    l[a] *= alpha;
+                    for (int c = 0; c < d; ++c)
+                        acc[(size_t)a * d + c] *= alpha;
+                    for (int n = t0; n < t1; ++n) {
+                        double p = isinf(xa[n - t0]) ? 0.0 : exp2(xa[n - t0] - m_new);
+                        xa[n - t0] = p;       /* the block of P~ */
+                        l[a] += p;
+                        if (p > b)
+                            b = p;
+                    }
+                    m[a] = m_new;
+                }
+                if (b == 0.0)
+                    continue;
+                for (int a = 0; a < rows; ++a) {
+                    const double *xa = x + (size_t)a * W;
+                    for (int n = t0; n < t1; ++n) {
+                        double ph = sage_oracle_e4m3_decode(sage_oracle_e4m3_encode(xa[n - t0] * p_r / b));
+                        if (ph != 0.0) {
+                            const double *vn = Vd + (size_t)n * d;
+                            for (int c = 0; c < d; ++c)
+                                acc[(size_t)a * d + c] += b * ph * vn[c];
+                        }
+                    }
+                }
+            }
+            for (int a = 0; a < rows; ++a) {
+                int r = r0 + a;
+                if (r < row0 || r >= row1)
+                    continue;
+                for (int c = 0; c < d; ++c) {
+                    double o = acc[(size_t)a * d + c] * (double)dv[c] / (p_r * l[a]);
+                    out[(size_t)(r - row0) * d + c] = out_dtype < 0 ? o : sage_oracle_round16(o, out_dtype);
+                }
+            }
+        }
+        free(x);
+        free(acc);
+        free(m);
+        free(l);
+    }
+    free(Vd);
+}
+
 /* The same block-wise online softmax on UNQUANTISED double operands
  * (Section 2.1 without any quantiser: P^ := P~, all scales 1).  It exists so
  * that the tiling / online-softmax skeleton can be pinned against the plain
