@@ -19,9 +19,21 @@ notice, a row that concentrates on a few keys (the heavy-tailed workload) can mo
 size.  Everything else (l, alpha, the FP32 accumulation order of P^ V^) is 1e-6 relative and shows only
 as an occasional flip of the final 16-bit rounding, i.e. one unit in the last place.
 
-The limits below are set to at most ten times the worst value measured over all GPU tests of this
-repository (every element of the four large workloads included); the measured values are printed by
-every test that calls the gate.
+  differ    fraction of elements that are not the same 16-bit number (a wrong rounding mode in the
+            epilogue moves half of them by one unit and none of them further).
+
+The limits below are 2.5 to 4.5 times the worst value measured over all GPU tests of this repository
+(422 comparisons, every element of cfg2, cfg3, cfg4 and six heads of cfg5 among them):
+            worst measured                  limit
+  row_l1    3.0e-2 (one row of cfg5)        0.125 = one FP8 step of a weight that carries the whole row
+  max_abs   0.10   (an early causal row)    0.4
+  beyond    fp16 1.5e-2, bf16 3.0e-3        fp16 4e-2, bf16 8e-3   (fp16's ulp is 8 times finer, so the
+  differ    fp16 8.9e-2, bf16 2.2e-2        fp16 0.25, bf16 0.06    same flips show 5 times as often)
+What the row bound cannot see: one key of average weight missing from ONE row of thousands of keys moves
+that row by 5e-3, the size of one legitimate FP8 flip.  A mask that is off by one hits every row of a
+diagonal or tail tile, though, and among them rows with few keys, which the bound does catch
+(tests/test_parity_gate.py plants both).  Every test that calls the gate prints its measured values;
+SAGE_GATE_LOG=<file> collects them.
 """
 from __future__ import annotations
 
@@ -32,10 +44,10 @@ import numpy as np
 COS_MIN = 0.9999          # benchmark definition
 REL_L1_MAX = 1e-3         # benchmark definition
 ROW_L1_MAX = 0.125        # worst single row: one FP8 step (2^-3) of a weight that carries the whole row
-MAX_ABS_MAX = 0.5         # largest |difference| in units of its row's RMS
+MAX_ABS_MAX = 0.4         # largest |difference| in units of its row's RMS
 BEYOND_ULP_MAX = {"fp16": 4e-2, "bf16": 8e-3}   # fraction of elements more than one 16-bit ulp apart
 BEYOND_ULP_MIN_COUNT = 16                        # ... a handful is always tolerated (blocks of a few rows)
-DIFFER_MAX = {"fp16": 0.5, "bf16": 0.5}         # fraction of elements that are not the same 16-bit number
+DIFFER_MAX = {"fp16": 0.25, "bf16": 0.06}        # fraction of elements that are not the same 16-bit number
 DIFFER_MIN_COUNT = 64
 
 _MANT = {"fp16": 10, "bf16": 7}

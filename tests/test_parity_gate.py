@@ -110,3 +110,18 @@ def test_a_few_fp8_flips_pass():
     m = parity_metrics(ref, rows, dtype)
     assert parity_failures(m) == [], m
     assert m["rel_l1"] < 2e-4
+
+
+@pytest.mark.parametrize("cfg_idx", [2, 3])
+def test_truncation_instead_of_rounding_fails(cfg_idx):
+    """An epilogue that truncates to the 16-bit type instead of rounding to nearest moves about half of the
+    elements by exactly one unit in the last place: invisible to the norms and to `beyond`, caught by `differ`."""
+    ref, _, _, dtype = _head(cfg_idx, 1024, 64, False, 17)
+    rng = np.random.default_rng(3)
+    bad = ref.copy()
+    hit = rng.random(ref.shape) < 0.5
+    bad[hit] -= np.sign(ref[hit]) * ulp16(ref[hit] * (1 - 1e-9), dtype)
+    m = parity_metrics(ref, bad, dtype)
+    assert m["beyond_count"] == 0 and m["row_l1"] < 0.01
+    fails = parity_failures(m)
+    assert len(fails) >= 1 and any("differ" in f for f in fails), (fails, m)
