@@ -27,13 +27,36 @@ if ROOT not in sys.path:
 PEAK_MFMA_8BIT = 5.0e15      # INT8 and FP8 dense, op/s
 PEAK_HBM = 8.0e12            # B/s
 
-# HBM traffic of one attention-kernel launch measured with rocprofv3 --pmc
-# (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); filled from
-# the summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/attn_kernel_cfg5_counters.md: 885116 KiB x 2.0 fetched + 196608 KiB x 1.0 written
-    "cfg5": int(885116 * 1024 * 2.0 + 196608 * 1024 * 1.0),
+# What rocprofv3 measured for the attention kernel on a workload (summaries under profiles/): HBM traffic of one
+# launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size) and, per wavefront and 128-key step,
+# the vector instructions issued, how many of them are MFMA, and how many run at half rate (exp, FP8 pack).
+# Only workloads that were profiled have an entry; everything derived from a missing entry is null in the
+# JSON line.  `valu_busy` / `mfma_busy` are SQ_ACTIVE_INST_VALU and SQ_VALU_MFMA_BUSY_CYCLES as fractions of
+# the kernel's SIMD time.
+PROFILED = {
+    "cfg5": dict(source="profiles/attn_kernel_cfg5_counters.md",
+                 traffic=int(885116 * 1024 * 2.0 + 196608 * 1024 * 1.0),
+                 valu_per_step=230.3, mfma_i8=16, mfma_f8=8, half_rate=49.2, valu_busy=0.91, mfma_busy=0.41),
+    "cfg3": dict(source="profiles/attn_kernel_cfg5_counters.md (section cfg3)", traffic=None,
+                 valu_per_step=218.6, mfma_i8=8, mfma_f8=4, half_rate=49.2, valu_busy=0.99, mfma_busy=0.23),
 }
+
+
+def alu_bound(prof):
+    """The co-limit of the MFMA roofline: the vector-ALU issue port, which MFMA and ordinary vector
+    instructions share.  Port cycles per wavefront-step from the measured instruction mix -- 4 cycles per
+    full-rate instruction and per 4-pass MFMA (INT8 16x16x64), 8 per half-rate instruction and per 8-pass MFMA
+    (FP8 16x16x128) -- against the MFMA pipe's own cycles for the same step (16 and 32 per instruction): their
+    ratio is the fraction of the MFMA peak this instruction mix can reach at equal clock."""
+    if not prof:
+        return None
+    n_mfma = prof["mfma_i8"] + prof["mfma_f8"]
+    other = prof["valu_per_step"] - n_mfma
+    port = 4.0 * (other - prof["half_rate"]) + 8.0 * prof["half_rate"] + 4.0 * prof["mfma_i8"] + 8.0 * prof["mfma_f8"]
+    pipe = 16.0 * prof["mfma_i8"] + 32.0 * prof["mfma_f8"]
+    return {"port_cycles_per_wavefront_step": round(port, 1), "mfma_cycles_per_wavefront_step": pipe,
+            "frac_of_peak_allowed": round(pipe / port, 4), "peak_allowed": round(PEAK_MFMA_8BIT / 1e12 * pipe / port, 1),
+            "unit": "TFLOP/s", "instruction_mix_from": prof["source"]}
 
 
 def main():
@@ -49,6 +72,11 @@ def main():
     ap.add_argument("--staged-q", action="store_true",
                     help="quantise Q with the stand-alone kernel (sage_quant_q + sage_attn_fwd_quantized) instead "
                          "of inside the attention kernel; same result bit for bit, for comparison")
+    ap.add_argument("--no-mfma-peak", action="store_true",
+                    help="skip the live measurement of the matrix-pipe rate (roofline.peak_measured)")
+    ap.add_argument("--mfma-table", action="store_true",
+                    help="only measure the matrix-pipe rates (INT8 16x16x64, FP8 16x16x128, FP8 16x16x32, the "
+                         "attention kernel's mix) with the library's MFMA-only kernel, print them as JSON and exit")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of Q (2E bytes read, 2E written) before the timed loop: "
                          "the known-size kernel that FETCH_SIZE / WRITE_SIZE counter runs are scaled by")
@@ -69,9 +97,16 @@ def main():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         sys.exit(2)
     sage.lib()
-    cfg = {c.name: c for c in wl.CONFIGS}[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.mfma_table:
+        names = ["int8_16x16x64", "fp8_16x16x128_f8f6f4", "fp8_16x16x32", "attention_mix_2xint8_1xfp8"]
+        for _ in range(2):      # the first round warms the clock up
+            rates = {n: round(sage.diag_mfma_rate(k, iters=8192, workgroups=2048, repeats=5) / 1e12, 1)
+                     for k, n in enumerate(names)}
+        print(json.dumps({"mfma_rate_TOPS": rates, "published_peak_TOPS": PEAK_MFMA_8BIT / 1e12}), flush=True)
+        return
+    cfg = {c.name: c for c in wl.CONFIGS}[args.config]
 
     t0 = time.time()
     q_h, k_h, v_h = wl.generate(cfg)
@@ -144,6 +179,11 @@ def main():
     # K and V: 2 bytes read + 1 byte written per element (Q is quantised inside the attention kernel)
     quant_gbs = (9.0 if args.staged_q else 6.0) * E / (quant_ms * 1e-3) / 1e9 if quant_ms > 0 else None
 
+    prof = PROFILED.get(cfg.name)
+    # the matrix-pipe rate this GPU sustains on the kernel's own instruction mix (two INT8 16x16x64 per FP8
+    # 16x16x128), measured now, on the warm GPU, with the library's MFMA-only kernel
+    peak_measured = None if args.no_mfma_peak else sage.diag_mfma_rate(3) / 1e12
+
     result = {
         "metric": "attention TOPS (4*B*H*N^2*d/s, halved when causal), quantisation + attention",
         "value": round(tops, 2),
@@ -169,10 +209,16 @@ def main():
             "peak": PEAK_MFMA_8BIT / 1e12,
             "unit": "TFLOP/s",
             "frac": round(attn_tops * 1e12 / PEAK_MFMA_8BIT, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "traffic": prof["traffic"] if prof else None,
             "kernel_ms": round(attn_ms, 4),
-            # what holds the kernel below the MFMA roofline (rocprofv3 counters, profiles/attn_kernel_cfg5_counters.md)
-            "limiter": "vector-ALU issue port (softmax arithmetic shares it with MFMA issue): 91 % busy, MFMA pipe 41 %",
+            # measured in this run: MFMA-only kernel, same instruction mix (null with --no-mfma-peak)
+            "peak_measured": round(peak_measured, 1) if peak_measured else None,
+            "frac_of_peak_measured": round(attn_tops / peak_measured, 4) if peak_measured else None,
+            # from the rocprofv3 counters of this workload (null for a workload that was not profiled)
+            "alu_bound": alu_bound(prof),
+            "limiter": (f"vector-ALU issue port (softmax arithmetic shares it with MFMA issue): "
+                        f"{100 * prof['valu_busy']:.0f} % busy, MFMA pipe {100 * prof['mfma_busy']:.0f} % "
+                        f"[{prof['source']}]") if prof else None,
         },
         "quant_stage": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_gbs, 1) if quant_gbs else None,
                         "frac_of_hbm_peak": round(quant_gbs * 1e9 / PEAK_HBM, 4) if quant_gbs else None},

@@ -249,6 +249,21 @@ int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out
                           int causal, float sm_scale, void *stream, sage_dtype dt,
                           void *workspace, size_t workspace_bytes);
 
+/* ---- measurement aid -------------------------------------------------- */
+
+/*
+ * Not a step of the method: launches a kernel that only issues the matrix instructions of the attention
+ * kernel, back to back on independent accumulators (4 wavefronts per workgroup, 8 accumulators each,
+ * `iters` rounds), so that a benchmark can time it (events on `stream`) and state throughput against the
+ * matrix-pipe rate the GPU at hand sustains, next to the published peak.
+ *   kind   0: INT8 16x16x64 (the Q^ K^T product), 1: FP8 16x16x128 (the P^ V^ product),
+ *          2: the older FP8 16x16x32 form, 3: the attention kernel's mix (two of kind 0 per one of kind 1)
+ *   sink   device, one float (never written in practice; keeps the arithmetic alive)
+ *   ops_per_launch  host, receives the operation count (2 per multiply-add) of the launch
+ * Returns SAGE_EINVAL for a bad argument, SAGE_EHIP if the launch failed.
+ */
+int sage_diag_mfma_rate(int kind, int iters, int workgroups, float *sink, double *ops_per_launch, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

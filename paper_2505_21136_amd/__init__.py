@@ -20,7 +20,7 @@ __all__ = [
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
     "sage_attn_fwd_strided", "sage_quant_kv", "sage_quant_kv_static", "workspace_bytes_gqa",
-    "v_fp8_to_token_major", "EXPORTS",
+    "v_fp8_to_token_major", "diag_mfma_rate", "EXPORTS",
 ]
 
 SAGE_F16, SAGE_BF16 = 0, 1
@@ -28,7 +28,7 @@ EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_w
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
            "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
-           "sage_quant_kv", "sage_quant_kv_static"]
+           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate"]
 
 
 class SageError(RuntimeError):
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.sage_quant_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_kv_static.restype = i
         L.sage_quant_kv_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp]
+        L.sage_diag_mfma_rate.restype = i
+        L.sage_diag_mfma_rate.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -204,6 +206,29 @@ def sage_quant_kv(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace:
                                v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(k), _stream(),
                                ws.data_ptr(), ws.numel()))
     return k_i8, k_scale, k_mean, v_fp8, v_scale
+
+
+def diag_mfma_rate(kind: int, iters: int = 4096, workgroups: int = 2048, repeats: int = 5) -> float:
+    """Sustained rate (operations per second) of the matrix instructions the attention kernel uses, measured
+    with HIP events around `sage_diag_mfma_rate` launches; kind as in include/sage.h.  A measurement aid."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ops = ctypes.c_double(0.0)
+    stream = torch.cuda.current_stream()
+
+    def launch():
+        _check(lib().sage_diag_mfma_rate(kind, iters, workgroups, sink.data_ptr(), ctypes.byref(ops), stream.cuda_stream))
+
+    for _ in range(3):
+        launch()
+    best = float("inf")
+    for _ in range(repeats):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        launch()
+        b.record(stream)
+        b.synchronize()
+        best = min(best, a.elapsed_time(b) * 1e-3)
+    return ops.value / best
 
 
 def sage_quant_kv_static(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, out=None):

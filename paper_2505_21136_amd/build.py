@@ -20,6 +20,7 @@ UNITS = [
     ("sage_quant.hip", ["-ffp-contract=off"]),
     ("sage_attn.hip", []),
     ("sage_api.hip", []),
+    ("sage_diag.hip", []),
 ]
 
 

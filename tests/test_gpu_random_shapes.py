@@ -1,6 +1,7 @@
-"""Seeded sweep over random shapes (1 to 2600 keys): batch, head grouping, N_q, N_k, head dimension, dtype, mask and
-memory layout are drawn independently, every case goes through the strided entry point and is compared
-with the oracle on the whole output."""
+"""Seeded sweep over random shapes (1 to 2600 keys): batch, head grouping, N_q, N_k, head dimension, value
+distribution with its dtype (the normal fp16 and bf16 workloads, and the heavy-tailed one: Student-t queries, four
+K channels x 20), mask and memory layout are drawn independently, every case goes through the strided entry point
+and is compared with the oracle on the whole output."""
 import numpy as np
 import pytest
 import torch
@@ -26,7 +27,7 @@ def _cases(n, seed):
         if rng.random() < 0.15:
             nq = int(rng.integers(nk, nk + 200))          # more queries than keys: non-causal only
         causal = bool(rng.random() < 0.5) and nk >= nq
-        out.append((i, int(rng.integers(1, 3)), hkv * group, hkv, nq, nk, d, int(rng.choice([1, 3])), causal,
+        out.append((i, int(rng.integers(1, 3)), hkv * group, hkv, nq, nk, d, int(rng.choice([1, 3, 5])), causal,
                     str(rng.choice(["bhnd", "bnhd"]))))
     return out
 
@@ -34,9 +35,11 @@ def _cases(n, seed):
 @pytest.mark.parametrize("i,B,Hq,Hkv,Nq,Nk,d,idx,causal,layout", _cases(60, 20250521))
 def test_random_shape(i, B, Hq, Hkv, Nq, Nk, d, idx, causal, layout):
     base = wl.CONFIGS[idx - 1]
-    say(f"[random] #{i} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} {base.dtype} causal={causal} {layout}")
-    q, _, _ = wl.generate(wl.Workload("q", base.index, B, Hq, Nq, d, False, base.dtype), seed=wl.SEED0 + 700 + i)
-    _, k, v = wl.generate(wl.Workload("kv", base.index, B, Hkv, Nk, d, False, base.dtype), seed=wl.SEED0 + 800 + i)
+    say(f"[random] #{i} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} {base.name}-like {base.dtype} causal={causal} {layout}")
+    q, _, _ = wl.generate(wl.Workload("q", base.index, B, Hq, Nq, d, False, base.dtype, base.q_dist,
+                                      base.k_outlier_channels), seed=wl.SEED0 + 700 + i)
+    _, k, v = wl.generate(wl.Workload("kv", base.index, B, Hkv, Nk, d, False, base.dtype, base.q_dist,
+                                      base.k_outlier_channels), seed=wl.SEED0 + 800 + i)
     sm = np.float32(1.0 / np.sqrt(d))
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     if layout == "bnhd":
