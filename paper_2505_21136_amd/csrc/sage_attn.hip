@@ -251,6 +251,8 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     __shared__ __attribute__((aligned(1024))) uint8_t ldsK[2][TILE];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsV[2][TILE];
     __shared__ float q_wave_max[NWAVE];
+    // per wavefront: the de-quantisation constants (c, kh, kl, -) of 64 consecutive K blocks (32 key steps)
+    __shared__ __attribute__((aligned(16))) float4 cst_lds[NWAVE][64];
     __shared__ __attribute__((aligned(16))) float dv_lds[D];  // delta_V of this head, for the epilogue
 
     const int tid = threadIdx.x;
@@ -370,7 +372,6 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             }
         }
     }
-    float cvec = 0.0f;  // lane i: constant of K block 64*(j/32) + i, refreshed every 32 steps
     const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
     float m[NQ], l[NQ], alpha[NQ];
@@ -496,16 +497,17 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         // first when both want the vector issue port
         __builtin_amdgcn_s_setprio(1);
         const int key0 = j * kW;
-        // de-quantisation constants of the two K blocks of this step
+        // de-quantisation constants of the two K blocks of this step: every 32 steps each lane computes the
+        // constants of one K block (c, and the exact split -K*c = kh + kl) and parks them in this wavefront's own
+        // strip of LDS; a step then fetches its two blocks with two broadcast reads and no vector arithmetic
         if ((j & 31) == 0) {
             const int blk = min(64 * (j >> 5) + lane, nKblk - 1);
-            cvec = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk]);
+            const float c = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk]);
+            const float kh = -kMagicF * c;
+            cst_lds[wave][lane] = make_float4(c, kh, __builtin_fmaf(-kMagicF, c, -kh), 0.0f);
         }
-        float c0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j) & 63));
-        float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), (2 * j + 1) & 63));
-        asm volatile("" : "+v"(c0), "+v"(c1));  // keep the constants in vector registers
-        const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;  // -K*c = kh + kl exactly
-        const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
+        const float4 k0 = cst_lds[wave][(2 * j) & 63], k1 = cst_lds[wave][(2 * j + 1) & 63];
+        float c0 = k0.x, c1 = k1.x, kh0 = k0.y, kh1 = k1.y, kl0 = k0.z, kl1 = k1.z;
         const bool masked_step = (key0 + kW > Nk) || (CAUSAL && key0 + kW - 1 > row0 + shift);
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
