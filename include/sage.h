@@ -143,7 +143,7 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
 /*
  * sage_quant_kv for callers that cannot allocate and have no workspace to hand over: code recorded
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
- * outputs bit for bit; the scratch (partial column statistics, about 12 bytes per channel and 256 tokens
+ * outputs bit for bit; the scratch (partial column statistics, about 12 bytes per channel and 1024 tokens
  * of every head) lives in a static device array inside the library, SAGE_STATIC_SCRATCH_BYTES (8 MiB)
  * per GPU, which each GPU the library runs on holds until the process ends.  The call allocates nothing
  * and frees nothing; on its first use on a device it looks up that device's copy of the array (the

@@ -11,7 +11,7 @@ constexpr int kBQ = 128;        // tokens per Q quantisation block
 constexpr int kBK = 64;         // tokens per K quantisation block
 constexpr int kW = 128;         // keys per online-softmax step (= V tile)
 #ifndef SAGE_STAT_ROWS
-#define SAGE_STAT_ROWS 256
+#define SAGE_STAT_ROWS 1024
 #endif
 constexpr int kStatRows = SAGE_STAT_ROWS;  // tokens per partial column statistic
 

@@ -39,7 +39,7 @@ def _run_static(k, v, v_r=4.5):
 
 
 def test_static_scratch_entry_point_equals_the_workspace_one_on_two_calls_in_a_row():
-    big = wl.Workload("big", 5, 2, 6, 5000, 128, False, "bf16", "student_t3", 4)     # 20 chunks per head
+    big = wl.Workload("big", 5, 2, 6, 5000, 128, False, "bf16", "student_t3", 4)     # 5 chunks per head
     small = wl.Workload("small", 3, 1, 3, 333, 64, False, "bf16")                     # fewer heads, ragged, other d
     for i, cfg in enumerate((big, small)):
         print(f"[no-alloc] call {i}: B{cfg.B} H{cfg.H} N{cfg.N} d{cfg.d} {cfg.dtype}", flush=True)
@@ -54,7 +54,7 @@ def test_static_scratch_entry_point_equals_the_workspace_one_on_two_calls_in_a_r
 
 
 def test_static_scratch_refuses_a_problem_beyond_its_size():
-    B, H, N, d = 1, 24, 65536, 128
+    B, H, N, d = 1, 24, 262144, 128
     assert sage.quant_workspace_bytes(B, H, N, d) > (8 << 20)
     # nothing may be touched: tiny buffers would be overrun by any launch, so the call must return first
     k = torch.zeros(16, dtype=torch.bfloat16, device=DEV)
