@@ -6,6 +6,9 @@ Only the test-suite, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 package imports nothing of the GPU library.  The passages of the paper each
 routine follows are cited in the C source.
 
+The 8+8 variant (INT8 Q.K^T) is the library's main path; the 4+8 variant (INT4 Q.K^T with smoothing of Q and
+the score correction it needs) has its routines in a section of its own.
+
 Parity status of the pins (see tests/test_oracle_*.py): every routine here is
 pinned by brute force, closed forms or an independent library rounding; the
 only figure with no pin is the accuracy *relative to full-precision attention*
@@ -59,7 +62,15 @@ def _load():
         lib.sage_oracle_quant_v.argtypes = [vp, c_i, c_i, c_f, vp, vp]
         lib.sage_oracle_attn_rows.restype = None
         lib.sage_oracle_attn_rows.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
-                                              c_i, c_i, c_i, c_i, c_i, c_i, vp, vp]
+                                              c_i, c_i, c_i, c_i, c_i, c_i, vp, vp, vp]
+        lib.sage_oracle_block_mean.restype = None
+        lib.sage_oracle_block_mean.argtypes = [vp, c_i, c_i, c_i, vp]
+        lib.sage_oracle_smooth.restype = None
+        lib.sage_oracle_smooth.argtypes = [vp, vp, c_i, c_i, c_i, c_i, vp]
+        lib.sage_oracle_quant_int.restype = None
+        lib.sage_oracle_quant_int.argtypes = [vp, vp, c_i, c_i, c_i, c_i, c_i, vp, vp]
+        lib.sage_oracle_delta_s.restype = None
+        lib.sage_oracle_delta_s.argtypes = [vp, vp, c_i, c_i, c_i, vp]
         lib.sage_oracle_attn_rows_blockmax.restype = None
         lib.sage_oracle_attn_rows_blockmax.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
                                                        c_i, c_i, c_i, c_i, c_i, c_i, vp]
@@ -152,15 +163,94 @@ def quant_v(V: np.ndarray, v_r: float = V_R):
 
 
 # --------------------------------------------------------------------------
+# 4+8 variant: smoothing of Q, INT4 codes, the score correction (one head)
+# --------------------------------------------------------------------------
+QMAX4 = 7      # INT4 codes lie in [-7, 7]
+
+
+def block_mean(Q: np.ndarray, block: int = BQ) -> np.ndarray:
+    """Per-block channel means of Q: [ceil(N/block), d] float32."""
+    Q = _c(Q, np.float32)
+    N, d = Q.shape
+    qbar = np.empty(((N + block - 1) // block, d), dtype=np.float32)
+    _load().sage_oracle_block_mean(_p(Q), N, d, block, _p(qbar))
+    return qbar
+
+
+def smooth(X: np.ndarray, mu: np.ndarray, block: int = BQ) -> np.ndarray:
+    """X - mu in binary32; mu is [d] (one vector) or [ceil(N/block), d] (one per block)."""
+    X, mu = _c(X, np.float32), _c(mu, np.float32)
+    N, d = X.shape
+    per_block = mu.ndim == 2
+    assert mu.shape == (((N + block - 1) // block, d) if per_block else (d,))
+    out = np.empty_like(X)
+    _load().sage_oracle_smooth(_p(X), _p(mu), int(per_block), N, d, block, _p(out))
+    return out
+
+
+def quant_int(X: np.ndarray, mu, block: int, qmax: int):
+    """Per-block integer codes in [-qmax, qmax] (one per byte) and scales of X - mu; mu as in smooth() or None."""
+    X = _c(X, np.float32)
+    N, d = X.shape
+    nb = (N + block - 1) // block
+    codes = np.empty((N, d), dtype=np.int8)
+    delta = np.empty(nb, dtype=np.float32)
+    mu_p, per_block = None, 0
+    if mu is not None:
+        mu = _c(mu, np.float32)
+        per_block = int(mu.ndim == 2)
+        assert mu.shape == ((nb, d) if per_block else (d,))
+        mu_p = _p(mu)
+    _load().sage_oracle_quant_int(_p(X), mu_p, per_block, N, d, block, int(qmax), _p(codes), _p(delta))
+    return codes, delta
+
+
+def delta_s(qbar: np.ndarray, k_smoothed: np.ndarray) -> np.ndarray:
+    """dS[i, n] = qbar[i] . K'[n] in double: [nQ, Nk]."""
+    qbar, Kp = _c(qbar, np.float32), _c(k_smoothed, np.float32)
+    nQ, d = qbar.shape
+    N = Kp.shape[0]
+    assert Kp.shape == (N, d)
+    dS = np.empty((nQ, N), dtype=np.float64)
+    _load().sage_oracle_delta_s(_p(qbar), _p(Kp), nQ, N, d, _p(dS))
+    return dS
+
+
+def quantize_head_4bit(q, k, v, *, v_r: float = V_R, bq: int = BQ, bk: int = BK):
+    """Quantisation stage of the 4+8 variant for one head (q [Nq,d]; k, v [Nk,d]): K smoothed by its channel
+    mean and Q by its block means, both to INT4 codes; V to FP8 as in 8+8; plus the score correction dS."""
+    mu = k_mean(k)
+    qbar = block_mean(q, bq)
+    q_codes, q_scale = quant_int(q, qbar, bq, QMAX4)
+    k_codes, k_scale = quant_int(k, mu, bk, QMAX4)
+    v_codes, v_scale = quant_v(v, v_r)
+    return dict(k_mean=mu, q_mean=qbar, q_codes=q_codes, q_scale=q_scale, k_codes=k_codes, k_scale=k_scale,
+                v_codes=v_codes, v_scale=v_scale, dS=delta_s(qbar, smooth(k, mu)))
+
+
+def sage_attention_head_4bit(q, k, v, *, causal: bool, sm_scale: float, out_dtype: str, p_r: float = P_R,
+                             v_r: float = V_R, bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
+                             quant=None):
+    """Whole 4+8 path for one head; returns (output rows as float64, quantised operands)."""
+    if quant is None:
+        quant = quantize_head_4bit(q, k, v, v_r=v_r, bq=bq, bk=bk)
+    out = attn_rows(quant["q_codes"], quant["k_codes"], quant["v_codes"], quant["q_scale"], quant["k_scale"],
+                    quant["v_scale"], causal=causal, sm_scale=sm_scale, p_r=p_r, bq=bq, bk=bk, w=w, row0=row0,
+                    row1=row1, out_dtype=out_dtype, dS=quant["dS"])
+    return out, quant
+
+
+# --------------------------------------------------------------------------
 # attention stage (one head)
 # --------------------------------------------------------------------------
 def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: float = P_R,
               bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
-              out_dtype="bf16", want_p: bool = False, delta_p: str = "static"):
+              out_dtype="bf16", want_p: bool = False, delta_p: str = "static", dS=None):
     """Quantised attention of query rows [row0, row1): Q^ is [Nq, d], K^ and V^ are [Nk, d].
 
     delta_p = "static" (the method as built: delta_P = 1/P_r) or "block_max" (Section 3.1 Eq. 2 read literally:
-    delta_P = max(P~)/P_r per (Q block x key step); a study mode, CPU only)."""
+    delta_P = max(P~)/P_r per (Q block x key step); a study mode, CPU only).
+    dS: the score correction of the 4+8 variant, [ceil(Nq/bq), Nk] float64 (see delta_s), or None."""
     Qc, Kc = _c(Qc, np.int8), _c(Kc, np.int8)
     Vc = _c(Vc, np.uint8)
     dq, dk, dv = _c(dq, np.float32), _c(dk, np.float32), _c(dv, np.float32)
@@ -174,6 +264,9 @@ def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: flo
     assert 0 <= row0 <= row1 <= Nq
     code = {"fp16": 0, "bf16": 1, None: -1}[out_dtype]
     out = np.empty((row1 - row0, d), dtype=np.float64)
+    if dS is not None:
+        dS = _c(dS, np.float64)
+        assert dS.shape == ((Nq + bq - 1) // bq, Nk) and delta_p == "static"
     if delta_p == "block_max":
         assert not want_p
         _load().sage_oracle_attn_rows_blockmax(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
@@ -183,7 +276,7 @@ def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: flo
     P = np.empty((row1 - row0, Nk), dtype=np.float64) if want_p else None
     _load().sage_oracle_attn_rows(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
                                   float(sm_scale), float(p_r), bq, bk, w, row0, row1, code,
-                                  _p(out), _p(P) if want_p else None)
+                                  _p(out), _p(P) if want_p else None, _p(dS) if dS is not None else None)
     return (out, P) if want_p else out
 
 

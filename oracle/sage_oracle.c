@@ -20,6 +20,9 @@
  *     Section 3, first paragraph (the paper names the step, gives no formula;
  *     the per-(batch, head, channel) mean over all N tokens is the reading
  *     taken here);
+ *   - the "4+8" variant (INT4 Q.K^T, Section 2.1 "INT4/INT8", Section 3 "smoothing of Q and K",
+ *     Section 4.1 "SageAttn2++(4+8)"): the routines marked 4+8 below; the paper names its ingredients and
+ *     prints no formula for them, the readings taken are stated at each routine;
  *   - accuracy metrics are NOT here (they are measurement, not method).
  *
  * Readings taken where the paper is silent (listed again in the design notes):
@@ -177,6 +180,98 @@ void sage_oracle_quant_int8(const float *X, const float *mu, int N, int d, int b
     }
 }
 
+/* ---- 4+8 variant: smoothing of Q and INT4 codes ----------------------------------------------------- */
+
+/* Smoothing statistic of Q (Section 3 names "smoothing of Q and K"; reading: what is subtracted from Q is
+ * the mean of each Q block, per channel, over the block's valid tokens):
+ *   qbar[i][c] = mean over rows r of block i of Q[r][c];  double sum, one rounding to binary32.            */
+void sage_oracle_block_mean(const float *Q, int N, int d, int block, float *qbar)
+{
+    int nb = (N + block - 1) / block;
+    for (int i = 0; i < nb; ++i) {
+        int r0 = i * block;
+        int r1 = r0 + block < N ? r0 + block : N;
+        for (int c = 0; c < d; ++c) {
+            double s = 0.0;
+            for (int r = r0; r < r1; ++r)
+                s += (double)Q[(size_t)r * d + c];
+            qbar[(size_t)i * d + c] = (float)(s / (double)(r1 - r0));
+        }
+    }
+}
+
+/* X' = X - mu as binary32 values (one correctly rounded subtraction per element).  mu_per_block = 0: one
+ * vector mu[d] for all rows (K smoothing); otherwise mu[i][d] for the rows of block i of `block` rows
+ * (Q smoothing).                                                                                          */
+void sage_oracle_smooth(const float *X, const float *mu, int mu_per_block, int N, int d, int block, float *out)
+{
+    for (int n = 0; n < N; ++n) {
+        const float *m = mu + (mu_per_block ? (size_t)(n / block) * d : 0);
+        for (int c = 0; c < d; ++c)
+            out[(size_t)n * d + c] = X[(size_t)n * d + c] - m[c];
+    }
+}
+
+/* Per-block integer quantisation with a symmetric range [-qmax, qmax] (Section 2.1: "INT4/INT8 with
+ * per-block granularity", delta = max|X| / qmax with qmax = 127 printed for INT8; reading for INT4:
+ * qmax = 7).  Same binary32 steps as sage_oracle_quant_int8: a = max|X'|, delta = a/qmax, r = qmax/a,
+ * code = round(X' * r); X' = X - mu with mu as in sage_oracle_smooth (NULL: no smoothing).  The codes are
+ * returned one per byte whatever qmax is.                                                                 */
+void sage_oracle_quant_int(const float *X, const float *mu, int mu_per_block, int N, int d, int block,
+                           int qmax, int8_t *codes, float *delta)
+{
+    int nb = (N + block - 1) / block;
+    float fq = (float)qmax;
+    for (int j = 0; j < nb; ++j) {
+        int n0 = j * block;
+        int n1 = n0 + block < N ? n0 + block : N;
+        const float *m = mu ? mu + (mu_per_block ? (size_t)j * d : 0) : NULL;
+        float a = 0.0f;
+        for (int n = n0; n < n1; ++n)
+            for (int c = 0; c < d; ++c) {
+                float x = X[(size_t)n * d + c];
+                if (m)
+                    x = x - m[c];
+                float ax = fabsf(x);
+                if (ax > a)
+                    a = ax;
+            }
+        if (a == 0.0f) {
+            delta[j] = 0.0f;
+            for (int n = n0; n < n1; ++n)
+                memset(codes + (size_t)n * d, 0, (size_t)d);
+            continue;
+        }
+        delta[j] = a / fq;
+        float r = fq / a;
+        for (int n = n0; n < n1; ++n)
+            for (int c = 0; c < d; ++c) {
+                float x = X[(size_t)n * d + c];
+                if (m)
+                    x = x - m[c];
+                float y = x * r;
+                codes[(size_t)n * d + c] = (int8_t)nearbyintf(y);
+            }
+    }
+}
+
+/* What smoothing of Q removes from the scores has to be put back (Section 3 keeps the smoothing of
+ * SageAttention2; reading): with Q' = Q - qbar_i on block i,
+ *     Q K'^T = Q' K'^T + qbar_i K'^T,
+ * the first product is the quantised one and the second,
+ *     dS[i][n] = sum_c qbar[i][c] * K'[n][c],        K' = K - mu_K (the smoothed, UNquantised keys),
+ * is evaluated in full precision (double here) and added to the de-quantised scores.                      */
+void sage_oracle_delta_s(const float *qbar, const float *Kp, int nQ, int N, int d, double *dS)
+{
+    for (int i = 0; i < nQ; ++i)
+        for (int n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c)
+                s += (double)qbar[(size_t)i * d + c] * (double)Kp[(size_t)n * d + c];
+            dS[(size_t)i * N + n] = s;
+        }
+}
+
 /* Per-channel FP8 quantisation of V (Section 2.1 and Eq. (2)):
  *   a_c = max_n |V[n][c]|,  delta_V[c] = a_c / V_r,  V^ = e4m3(V * (V_r/a_c)).
  * Codes are returned token-major, codes[n][c].                               */
@@ -230,12 +325,17 @@ void sage_oracle_quant_v(const float *V, int N, int d, float v_r, uint8_t *codes
  * same quantised K, V head.
  *
  * P_out, if not NULL, receives the normalised probabilities 2^(x - m_final)/l
- * as (row1-row0) x Nk doubles (test use only: rows must sum to one).         */
+ * as (row1-row0) x Nk doubles (test use only: rows must sum to one).
+ *
+ * dS, if not NULL, is the score correction of the 4+8 variant (see sage_oracle_delta_s), [ceil(Nq/BQ)][Nk]
+ * doubles in the units of Q K^T: the de-quantised score of (r, n) becomes
+ *     S_int * delta_Q * delta_K + dS[r/BQ][n]      before the factor sm_scale * log2 e.
+ * The integer codes may come from either quantiser (INT8 or INT4 range); nothing else differs.              */
 void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc,
                            const float *dq, const float *dk, const float *dv,
                            int Nq, int Nk, int d, int causal, double sm_scale, double p_r,
                            int BQ, int BK, int W, int row0, int row1, int out_dtype,
-                           double *out, double *P_out)
+                           double *out, double *P_out, const double *dS)
 {
     const int N = Nk;
     const int shift = Nk - Nq; /* causal alignment */
@@ -270,6 +370,8 @@ void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc
                         s += (int32_t)qr[c] * (int32_t)kn[c];
                     double cst = (double)dq[r / BQ] * (double)dk[n / BK] * sm_scale * SAGE_ORACLE_LOG2E;
                     x[n - t0] = (double)s * cst;
+                    if (dS)
+                        x[n - t0] += dS[(size_t)(r / BQ) * N + n] * (sm_scale * SAGE_ORACLE_LOG2E);
                     if (x[n - t0] > mx)
                         mx = x[n - t0];
                 }
