@@ -249,6 +249,79 @@ int sage_attn_fwd_strided(const void *q, const void *k, const void *v, void *out
                           int causal, float sm_scale, void *stream, sage_dtype dt,
                           void *workspace, size_t workspace_bytes);
 
+/* ---- the 4+8 variant: INT4 Q K^T with smoothing of Q and K, FP8 P V ------------------------------------
+ *
+ * [Sec. 2.1 "INT4/INT8 with per-block granularity"; Sec. 3 "smoothing of Q and K"; Sec. 4.1 "SageAttn2++(4+8)".]
+ * The paper names the ingredients and prints no formula for them; this library takes:
+ *   INT4 codes   integers in [-7, 7], delta = max|X| / 7, same blocks and binary32 steps as the INT8 quantiser,
+ *                stored one code per byte (gfx950 has no INT4 matrix instruction: the codes run through the
+ *                INT8 one, so the variant buys no speed here and exists for completeness and accuracy studies);
+ *   K smoothing  as in 8+8 (per-head channel mean over all tokens);
+ *   Q smoothing  the mean of each block of SAGE_BQ query rows, per channel, over the block's valid rows
+ *                (double sum, one rounding to binary32), subtracted with one binary32 operation;
+ *   correction   what the Q smoothing removed is put back on the scores in full precision:
+ *                S = delta_Q delta_K Q^ K^^T + qbar_i . K'[n],  K' = K - mean_K (unquantised, FP32 here);
+ *   everything after the scores (online softmax, P~ to FP8, P^ V^, epilogue) as in 8+8.
+ * All calls take the grouped-query shapes of sage_attn_fwd_gqa (Hq = Hkv, Nq = Nk for plain self-attention).
+ */
+
+/* Bytes of the score-correction buffer: B*Hq*ceil(Nq/SAGE_BQ)*ceil(Nk/128)*128 floats (0: invalid sizes). */
+size_t sage_delta_s_bytes(int B, int Hq, int Nq, int Nk);
+/* Scratch needed by sage_attn_fwd_4bit. */
+size_t sage_workspace_bytes_4bit(int B, int Hq, int Hkv, int Nq, int Nk, int d);
+
+/*
+ * Block means of Q and, optionally, the stand-alone INT4 codes of Q minus its block means.
+ *   q       device, [B,H,N,d] of `dt`                                              (in)
+ *   q_mean  device, [B,H,ceil(N/SAGE_BQ),d] float                                  (out)
+ *   q_i4    device, [B,H,N,d] int8 codes in [-7,7], or NULL                        (out)
+ *   q_scale device, [B,H,ceil(N/SAGE_BQ)] float, NULL exactly when q_i4 is NULL    (out)
+ * (The attention call quantises Q itself from q and q_mean; the stand-alone codes exist so that they can be
+ * compared bit for bit.)
+ */
+int sage_quant_q4(const void *q, float *q_mean, int8_t *q_i4, float *q_scale,
+                  int B, int H, int N, int d, sage_dtype dt, void *stream);
+
+/* sage_quant_kv with INT4 codes for K (range [-7,7], one per byte); V as in 8+8.  Arguments as sage_quant_kv. */
+int sage_quant_kv4(const void *k, const void *v, int8_t *k_i4, float *k_scale, float *k_mean,
+                   uint8_t *v_fp8, float *v_scale, float v_r,
+                   int B, int H, int N, int d, sage_dtype dt, void *stream,
+                   void *workspace, size_t workspace_bytes);
+
+/*
+ * The score correction in the units of the softmax exponent:
+ *   dsx[b,hq,i,T,pos] = (sum_c q_mean[b,hq,i,c] * (K[b,hkv,n,c] - k_mean[b,hkv,c])) * sm_scale * log2(e)
+ * for Q block i and key n = 128*T + 16*t + 4*g + j stored at pos = 32*g + 4*t + j (the order in which a lane
+ * of the attention kernel holds its scores); keys >= Nk hold 0.  FP32 arithmetic.
+ *   k       device, [B,Hkv,Nk,d] of `dt` (the unquantised keys)       (in)
+ *   k_mean  device, [B,Hkv,d] float, from sage_quant_kv4              (in)
+ *   q_mean  device, [B,Hq,ceil(Nq/SAGE_BQ),d] float                   (in)
+ *   dsx     device, sage_delta_s_bytes() bytes                        (out)
+ *   causal  1: (Q block, key tile) pairs the end-aligned mask hides completely may be left unwritten
+ *   sm_scale as for the attention calls (the same value must be passed there)
+ */
+int sage_delta_s(const void *k, const float *k_mean, const float *q_mean, float *dsx,
+                 int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale,
+                 sage_dtype dt, void *stream);
+
+/*
+ * Fused attention of the 4+8 variant on unquantised Q (smoothed and quantised to INT4 in the kernel's prologue
+ * with the block means given), INT4 K^, FP8 V^ and the score correction.  Output, mask, sm_scale, p_r as for
+ * sage_attn_fwd_kvquantized_gqa.
+ */
+int sage_attn_fwd_q4(const void *q, const float *q_mean, const int8_t *k_i4, const uint8_t *v_fp8,
+                     const float *k_scale, const float *v_scale, const float *dsx, void *out,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale, float p_r,
+                     sage_dtype dt, void *stream);
+
+/*
+ * The whole forward pass of the 4+8 variant: sage_quant_kv4 + sage_quant_q4 (means only) + sage_delta_s +
+ * sage_attn_fwd_q4 with the default ranges; workspace >= sage_workspace_bytes_4bit(), 256-byte aligned.
+ */
+int sage_attn_fwd_4bit(const void *q, const void *k, const void *v, void *out,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale,
+                       void *stream, sage_dtype dt, void *workspace, size_t workspace_bytes);
+
 /* ---- measurement aid -------------------------------------------------- */
 
 /*

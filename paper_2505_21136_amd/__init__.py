@@ -20,7 +20,8 @@ __all__ = [
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
     "sage_attn_fwd_strided", "sage_quant_kv", "sage_quant_kv_static", "workspace_bytes_gqa",
-    "v_fp8_to_token_major", "diag_mfma_rate", "EXPORTS",
+    "v_fp8_to_token_major", "diag_mfma_rate", "EXPORTS", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s",
+    "sage_attn_fwd_q4", "sage_attn_fwd_4bit", "workspace_bytes_4bit", "delta_s_to_key_order",
 ]
 
 SAGE_F16, SAGE_BF16 = 0, 1
@@ -28,7 +29,9 @@ EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_w
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
            "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
-           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate"]
+           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate", "sage_delta_s_bytes",
+           "sage_workspace_bytes_4bit", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s", "sage_attn_fwd_q4",
+           "sage_attn_fwd_4bit"]
 
 
 class SageError(RuntimeError):
@@ -81,6 +84,20 @@ def lib() -> ctypes.CDLL:
         L.sage_quant_kv_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp]
         L.sage_diag_mfma_rate.restype = i
         L.sage_diag_mfma_rate.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.sage_delta_s_bytes.restype = sz
+        L.sage_delta_s_bytes.argtypes = [i, i, i, i]
+        L.sage_workspace_bytes_4bit.restype = sz
+        L.sage_workspace_bytes_4bit.argtypes = [i, i, i, i, i, i]
+        L.sage_quant_q4.restype = i
+        L.sage_quant_q4.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
+        L.sage_quant_kv4.restype = i
+        L.sage_quant_kv4.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp, vp, sz]
+        L.sage_delta_s.restype = i
+        L.sage_delta_s.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, vp]
+        L.sage_attn_fwd_q4.restype = i
+        L.sage_attn_fwd_q4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, vp]
+        L.sage_attn_fwd_4bit.restype = i
+        L.sage_attn_fwd_4bit.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, i, vp, sz]
         L.sage_quant_qk.restype = i
         L.sage_quant_qk.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, sz]
         L.sage_quant_v.restype = i
@@ -389,6 +406,98 @@ def sage_attn_fwd(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torch.Te
     _check(lib().sage_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d, int(causal),
                                float(sm_scale), _stream(), _dt(q), ws.data_ptr(), ws.numel()))
     return out
+
+
+# --------------------------------------------------------------------------
+# the 4+8 variant (INT4 Q K^T with smoothing of Q and K)
+# --------------------------------------------------------------------------
+def workspace_bytes_4bit(B, Hq, Hkv, Nq, Nk, d) -> int:
+    return int(lib().sage_workspace_bytes_4bit(B, Hq, Hkv, Nq, Nk, d))
+
+
+def sage_quant_q4(q: torch.Tensor, codes: bool = True):
+    """-> (q_mean [B,H,ceil(N/128),d], q_i4 [B,H,N,d] int8 in [-7,7], q_scale [B,H,ceil(N/128)]); the last two
+    are None with codes=False."""
+    _dev(q)
+    B, H, N, d = q.shape
+    nq = -(-N // 128)
+    q_mean = torch.empty((B, H, nq, d), dtype=torch.float32, device=q.device)
+    q_i4 = torch.empty((B, H, N, d), dtype=torch.int8, device=q.device) if codes else None
+    q_scale = torch.empty((B, H, nq), dtype=torch.float32, device=q.device) if codes else None
+    _check(lib().sage_quant_q4(q.data_ptr(), q_mean.data_ptr(), q_i4.data_ptr() if codes else None,
+                               q_scale.data_ptr() if codes else None, B, H, N, d, _dt(q), _stream()))
+    return q_mean, q_i4, q_scale
+
+
+def sage_quant_kv4(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace: torch.Tensor | None = None):
+    """sage_quant_kv with INT4 codes for K -> (k_i4, k_scale, k_mean, v_fp8, v_scale)."""
+    _dev(k, v)
+    if k.shape != v.shape or k.dtype != v.dtype:
+        raise SageError("k and v must share shape and dtype")
+    B, H, N, d = k.shape
+    dev = k.device
+    k_i4 = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    k_scale = torch.empty((B, H, -(-N // 64)), dtype=torch.float32, device=dev)
+    k_mean = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    v_fp8 = torch.empty((B, H, -(-N // 128), d, 128), dtype=torch.uint8, device=dev)
+    v_scale = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    ws = workspace if workspace is not None else _workspace(quant_workspace_bytes(B, H, N, d), dev)
+    _check(lib().sage_quant_kv4(k.data_ptr(), v.data_ptr(), k_i4.data_ptr(), k_scale.data_ptr(), k_mean.data_ptr(),
+                                v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(k), _stream(),
+                                ws.data_ptr(), ws.numel()))
+    return k_i4, k_scale, k_mean, v_fp8, v_scale
+
+
+def sage_delta_s(k: torch.Tensor, k_mean: torch.Tensor, q_mean: torch.Tensor, Nq: int, *, causal: bool,
+                 sm_scale: float = 0.0) -> torch.Tensor:
+    """The score correction in exponent units -> [B,Hq,ceil(Nq/128),ceil(Nk/128),128] float32 (lane order)."""
+    _dev(k, k_mean, q_mean)
+    B, Hkv, Nk, d = k.shape
+    Hq, nq = q_mean.shape[1], q_mean.shape[2]
+    dsx = torch.empty((B, Hq, nq, -(-Nk // 128), 128), dtype=torch.float32, device=k.device)
+    _check(lib().sage_delta_s(k.data_ptr(), k_mean.data_ptr(), q_mean.data_ptr(), dsx.data_ptr(), B, Hq, Hkv, Nq, Nk, d,
+                              int(causal), float(sm_scale), _dt(k), _stream()))
+    return dsx
+
+
+def sage_attn_fwd_q4(q, q_mean, k_i4, v_fp8, k_scale, v_scale, dsx, *, causal: bool, sm_scale: float = 0.0,
+                     p_r: float = 224.0, out: torch.Tensor | None = None):
+    _dev(q, q_mean, k_i4, v_fp8, k_scale, v_scale, dsx)
+    B, Hq, Nq, d = q.shape
+    _, Hkv, Nk, _ = k_i4.shape
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    _check(lib().sage_attn_fwd_q4(q.data_ptr(), q_mean.data_ptr(), k_i4.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
+                                  v_scale.data_ptr(), dsx.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d, int(causal),
+                                  float(sm_scale), float(p_r), _dt(q), _stream()))
+    return out
+
+
+def sage_attn_fwd_4bit(q, k, v, *, causal: bool, sm_scale: float = 0.0, out: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None):
+    """Whole forward pass of the 4+8 variant for q [B,Hq,Nq,d] and k, v [B,Hkv,Nk,d]."""
+    _dev(q, k, v)
+    B, Hq, Nq, d = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[3] != d or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise SageError("k and v must share a shape [B,Hkv,Nk,d] and the dtype of q")
+    _, Hkv, Nk, _ = k.shape
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    ws = workspace if workspace is not None else _workspace(workspace_bytes_4bit(B, Hq, Hkv, Nq, Nk, d), q.device)
+    _check(lib().sage_attn_fwd_4bit(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d,
+                                    int(causal), float(sm_scale), _stream(), _dt(q), ws.data_ptr(), ws.numel()))
+    return out
+
+
+def delta_s_to_key_order(dsx: torch.Tensor, Nk: int) -> torch.Tensor:
+    """Undo the lane order of the score-correction buffer: [B,Hq,nQ,T,128] -> [B,Hq,nQ,Nk] (layout bookkeeping
+    only).  Position 32*g + 4*t + j of a tile is key 16*t + 4*g + j."""
+    B, H, nq, T, _ = dsx.shape
+    x = dsx.reshape(B, H, nq, T, 4, 8, 4)            # [.., g, t, j]
+    x = x.permute(0, 1, 2, 3, 5, 4, 6)               # [.., t, g, j]
+    return x.reshape(B, H, nq, T * 128)[..., :Nk].contiguous()
 
 
 def v_fp8_to_token_major(v_fp8: torch.Tensor, N: int) -> torch.Tensor:

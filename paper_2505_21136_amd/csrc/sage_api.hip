@@ -129,6 +129,26 @@ FwdWorkspace fwd_layout(void *base, int B, int Hq, int Hkv, int Nq, int Nk, int 
     return w;
 }
 
+// Carving of the sage_attn_fwd_4bit workspace: the 8+8 layout plus the block means of Q and the score correction.
+struct Fwd4Workspace {
+    FwdWorkspace base;
+    float *q_mean, *dsx;
+    size_t bytes;
+};
+Fwd4Workspace fwd4_layout(void *base, int B, int Hq, int Hkv, int Nq, int Nk, int d) {
+    Fwd4Workspace w;
+    w.base = fwd_layout(base, B, Hq, Hkv, Nq, Nk, d);
+    char *p = static_cast<char *>(base);
+    size_t off = w.base.bytes;
+    const size_t BHq = (size_t)B * Hq, nQ = (size_t)sage::cdiv(Nq, sage::kBQ), nT = (size_t)sage::cdiv(Nk, sage::kW);
+    w.q_mean = reinterpret_cast<float *>(p + off);
+    off += align256(BHq * nQ * d * sizeof(float));
+    w.dsx = reinterpret_cast<float *>(p + off);
+    off += align256(BHq * nQ * nT * 128 * sizeof(float));
+    w.bytes = off;
+    return w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -259,6 +279,101 @@ int sage_quant_kv_static(const void *k, const void *v, int8_t *k_i8, float *k_sc
     const sage::Strides st = sage::contiguous_bhnd(H, N, d);
     return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
                                           dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+}
+
+/* ---- the 4+8 variant ---------------------------------------------------------------------------------- */
+
+size_t sage_workspace_bytes_4bit(int B, int Hq, int Hkv, int Nq, int Nk, int d) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, 0)) return 0;
+    return fwd4_layout(nullptr, B, Hq, Hkv, Nq, Nk, d).bytes;
+}
+
+size_t sage_delta_s_bytes(int B, int Hq, int Nq, int Nk) {
+    if (B < 1 || Hq < 1 || Nq < 1 || Nk < 1 || Nq > (1 << 22) || Nk > (1 << 22) || (size_t)B * Hq > 65535u) return 0;
+    return (size_t)B * Hq * sage::cdiv(Nq, sage::kBQ) * sage::cdiv(Nk, sage::kW) * 128 * sizeof(float);
+}
+
+int sage_quant_q4(const void *q, float *q_mean, int8_t *q_i4, float *q_scale, int B, int H, int N, int d,
+                  sage_dtype dt, void *stream) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !q_mean || !aligned16(q) || !aligned16(q_mean)) return SAGE_EINVAL;
+    if ((q_i4 == nullptr) != (q_scale == nullptr) || (q_i4 && !aligned16(q_i4))) return SAGE_EINVAL;
+    discard_pending_hip_error();
+    return from_hip(sage::launch_quant_q4(q, sage::contiguous_bhnd(H, N, d), q_mean, q_i4, q_scale, B, H, N, d,
+                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream)));
+}
+
+int sage_quant_kv4(const void *k, const void *v, int8_t *k_i4, float *k_scale, float *k_mean, uint8_t *v_fp8,
+                   float *v_scale, float v_r, int B, int H, int N, int d, sage_dtype dt, void *stream, void *workspace,
+                   size_t workspace_bytes) {
+    if (!shape_ok(B, H, N, d) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!k || !v || !k_i4 || !k_scale || !k_mean || !v_fp8 || !v_scale) return SAGE_EINVAL;
+    if (!(v_r > 0.0f) || !(v_r <= 448.0f)) return SAGE_EINVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_i4) || !aligned16(v_fp8) || !aligned16(v_scale) ||
+        !aligned16(k_mean))
+        return SAGE_EINVAL;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_quant_workspace_bytes(B, H, N, d))
+        return SAGE_EWORKSPACE;
+    const sage::QuantScratch ws = sage::quant_scratch_layout(workspace, B, H, N, d);
+    const sage::Strides st = sage::contiguous_bhnd(H, N, d);
+    discard_pending_hip_error();
+    return from_hip(sage::launch_quant_kv(k, st, v, st, k_i4, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,
+                                          dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws, true));
+}
+
+int sage_delta_s(const void *k, const float *k_mean, const float *q_mean, float *dsx, int B, int Hq, int Hkv, int Nq,
+                 int Nk, int d, int causal, float sm_scale, sage_dtype dt, void *stream) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!k || !k_mean || !q_mean || !dsx) return SAGE_EINVAL;
+    if (!aligned16(k) || !aligned16(k_mean) || !aligned16(q_mean) || !aligned16(dsx)) return SAGE_EINVAL;
+    sm_scale = scale_or_default(sm_scale, d);
+    discard_pending_hip_error();
+    return from_hip(sage::launch_delta_s(k, sage::contiguous_bhnd(Hkv, Nk, d), k_mean, q_mean, dsx, B, Hq, Hkv, Nq, Nk,
+                                         d, causal != 0, sm_scale, dt == SAGE_BF16, static_cast<hipStream_t>(stream)));
+}
+
+int sage_attn_fwd_q4(const void *q, const float *q_mean, const int8_t *k_i4, const uint8_t *v_fp8,
+                     const float *k_scale, const float *v_scale, const float *dsx, void *out, int B, int Hq, int Hkv,
+                     int Nq, int Nk, int d, int causal, float sm_scale, float p_r, sage_dtype dt, void *stream) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !q_mean || !k_i4 || !v_fp8 || !k_scale || !v_scale || !dsx || !out) return SAGE_EINVAL;
+    if (!aligned16(q) || !aligned16(q_mean) || !aligned16(k_i4) || !aligned16(v_fp8) || !aligned16(v_scale) ||
+        !aligned16(dsx) || !aligned16(out))
+        return SAGE_EINVAL;
+    if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
+    sm_scale = scale_or_default(sm_scale, d);
+    const sage::Strides st = sage::contiguous_bhnd(Hq, Nq, d);
+    discard_pending_hip_error();
+    return from_hip(sage::launch_attn(q, true, st, k_i4, v_fp8, nullptr, k_scale, v_scale, out, st, B, Hq, Hkv, Nq, Nk, d,
+                                      causal != 0, sm_scale, p_r, dt == SAGE_BF16, static_cast<hipStream_t>(stream),
+                                      q_mean, dsx));
+}
+
+int sage_attn_fwd_4bit(const void *q, const void *k, const void *v, void *out, int B, int Hq, int Hkv, int Nq, int Nk,
+                       int d, int causal, float sm_scale, void *stream, sage_dtype dt, void *workspace,
+                       size_t workspace_bytes) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !k || !v || !out) return SAGE_EINVAL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return SAGE_EINVAL;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < sage_workspace_bytes_4bit(B, Hq, Hkv, Nq, Nk, d))
+        return SAGE_EWORKSPACE;
+    sm_scale = scale_or_default(sm_scale, d);
+    const Fwd4Workspace w = fwd4_layout(workspace, B, Hq, Hkv, Nq, Nk, d);
+    const sage::QuantScratch qws = sage::quant_scratch_layout(w.base.quant, B, Hkv, Nk, d);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = dt == SAGE_BF16;
+    const sage::Strides qs = sage::contiguous_bhnd(Hq, Nq, d), ks = sage::contiguous_bhnd(Hkv, Nk, d);
+    discard_pending_hip_error();
+    hipError_t e = sage::launch_quant_kv(k, ks, v, ks, w.base.k_i8, w.base.k_scale, w.base.k_mean, w.base.v_fp8,
+                                         w.base.v_scale, 4.5f, B, Hkv, Nk, d, bf16, s, qws, true);
+    if (e == hipSuccess) e = sage::launch_quant_q4(q, qs, w.q_mean, nullptr, nullptr, B, Hq, Nq, d, bf16, s);
+    if (e == hipSuccess)
+        e = sage::launch_delta_s(k, ks, w.base.k_mean, w.q_mean, w.dsx, B, Hq, Hkv, Nq, Nk, d, causal != 0, sm_scale, bf16,
+                                 s);
+    if (e == hipSuccess)
+        e = sage::launch_attn(q, true, qs, w.base.k_i8, w.base.v_fp8, nullptr, w.base.k_scale, w.base.v_scale, out, qs, B,
+                              Hq, Hkv, Nq, Nk, d, causal != 0, sm_scale, 224.0f, bf16, s, w.q_mean, w.dsx);
+    return from_hip(e);
 }
 
 int sage_attn_fwd_quantized_gqa(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,

@@ -201,6 +201,72 @@ __device__ __forceinline__ float softmax_step(v4i (&s)[8], float c0, float c1, f
     return alpha;
 }
 
+// The same step for the 4+8 variant (INT4 codes, Q smoothed by its block means): the de-quantised score of a
+// key gets the correction term ds = (qbar . K'[n]) * sm_scale * log2(e) added, which differs from key to key,
+// so the step maximum is taken on the finished exponents x = c * S + ds (FP32) instead of on the integers:
+// per score one conversion, one FMA, half a max3, one addition, one exp2, one addition, half an FP8 pack.
+// s holds plain INT32 scores.  ds: this lane's 32 correction terms of the step (LDS), 8 x float4 in the order
+// of its scores.
+template <bool MASKED>
+__device__ __forceinline__ float softmax_step_q4(const v4i (&s)[8], float c0, float c1, float log2_pr, float &m, float &l,
+                                                 v8i &pb, int key_base, int lim, int t_lo, int t_hi,
+                                                 const float4 *__restrict__ ds) {
+    float mx0 = -INFINITY, mx1 = -INFINITY;
+    float xf[8][4];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        bool live = true;
+        if constexpr (MASKED) live = t < t_hi;
+        if (live) {
+            const float4 d4 = ds[t];
+            const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+            const float cb = t < 4 ? c0 : c1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int sv = s[t][i];
+                float x = __builtin_fmaf((float)sv, cb, dd[i]);
+                if constexpr (MASKED) {
+                    if (t >= t_lo && key_base + 16 * t + i > lim) x = -INFINITY;
+                }
+                xf[t][i] = x;
+                if (i < 2) mx0 = fmaxf(mx0, x); else mx1 = fmaxf(mx1, x);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xf[t][i] = -INFINITY;
+        }
+        // (keeps the compiler from fetching all 32 correction terms up front)
+        if (t == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+    const float mc = rowgroup_max(fmaxf(mx0, mx1));
+    const float m_new = fmaxf(m, mc);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    const float mo = log2_pr - m_new;  // P~ * P_r = 2^(x - m' + log2 P_r)
+    float lsum0 = -0.0f, lsum1 = -0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        if constexpr (MASKED) {
+            if (t >= t_hi) {
+                pb[t] = 0;
+                continue;
+            }
+        }
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(xf[t][i] + mo);  // a masked key: 2^(-inf) = 0
+        lsum0 += p[0] + p[1];
+        lsum1 += p[2] + p[3];
+        int w;  // both halves are overwritten below
+        asm volatile("" : "=v"(w));
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
+        pb[t] = w;
+    }
+    l = l * alpha + (lsum0 + lsum1);
+    m = m_new;
+    return alpha;
+}
+
 #if defined(__HIP_DEVICE_COMPILE__)
 // Enqueue piece k of the global -> LDS copy of one [128 x D]-byte tile (K^ or V^) of key step j.  A tile is
 // copied by the NW wavefronts of one group, CPG pieces each; a piece (one buffer load) moves 16 bytes per
@@ -233,12 +299,21 @@ __device__ __forceinline__ void issue_tile_piece(uint8_t *dst, const uint8_t *he
 // exactly one Q quantisation block, quantises it in its prologue (paper Sec. 2.1: per-block INT8,
 // delta = max|Q| / 127) with the same binary32 operations as the stand-alone quantiser, so codes
 // and scale are the same bits; Q^ and delta_Q then never touch memory.
-template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW>
-__global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
+//
+// Q4 (with QRAW): the 4+8 variant.  K^ holds INT4 codes (one per byte, same INT8 MFMA), Q is smoothed by the
+// block means `q_mean` before its INT4 quantisation (delta = max|Q - qbar| / 7), and the score correction
+// `dsx` (see softmax_step_q4) is added in the softmax part; everything else is shared with the 8+8 kernel.
+// (Its softmax part keeps the 32 exponents of a step in registers next to the scores they come from; at d = 128
+// that does not fit the 128 registers of four wavefronts per SIMD, so this one variant is built for two: one
+// workgroup per CU instead of two.)
+template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW, bool Q4>
+__global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_kernel(
     const void *__restrict__ Qsrc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
     uint16_t *__restrict__ out, Strides q_st, Strides o_st, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq,
-    int group, float sm_scale, float log2_pr, int nQtiles) {
+    int group, float sm_scale, float log2_pr, int nQtiles, const float *__restrict__ q_mean,
+    const float *__restrict__ dsx) {
+    static_assert(!Q4 || QRAW, "the 4+8 variant quantises Q in the kernel");
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
     constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
     constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
@@ -253,6 +328,8 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     __shared__ float q_wave_max[NWAVE];
     // per wavefront: the de-quantisation constants (c, kh, kl, -) of 64 consecutive K blocks (32 key steps)
     __shared__ __attribute__((aligned(16))) float4 cst_lds[NWAVE][64];
+    // 4+8 variant: the score-correction terms of three consecutive key steps (128 floats each, lane order)
+    __shared__ __attribute__((aligned(16))) float ds_lds[Q4 ? 3 : 1][128];
     __shared__ __attribute__((aligned(16))) float dv_lds[D];  // delta_V of this head, for the epilogue
 
     const int tid = threadIdx.x;
@@ -330,10 +407,23 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
     int my_steps = nsteps;
     if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
     if (row0 >= Nq) my_steps = 0;  // a wavefront without a valid row only takes part in the copies and barriers
+    // 4+8 variant: the correction terms of this Q block, [nT][128] floats; the first wavefront copies those of
+    // key step j into ds_lds[j % 3] with the K^ tile of that step (two 256-byte pieces, global -> LDS direct)
+    auto copy_ds = [&](int j) {
+        if constexpr (Q4) {
+            if (wave == 0 && j < nsteps) {
+                const float *src = dsx + (((size_t)bh * nQblk + qtile) * nT + j) * 128;
+                const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, 512, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)&ds_lds[j % 3][0], 4, lane * 4, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)&ds_lds[j % 3][64], 4, 256 + lane * 4, 0, 0, 0);
+            }
+        }
+    };
     if (grp == 0) {
 #pragma unroll
         for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], Kh, k_bytes, c_voff, wig, k, 0);
     }
+    copy_ds(0);
 
     // the lane's B operand of S^T = K^ Q^T: 16 consecutive channels (64*ch + 16*g ..) of query row lq
     v4i qreg[NQ][KC];
@@ -352,9 +442,22 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
                     qraw[qt][ch][h] = r < Nq ? *reinterpret_cast<const uint4 *>(Qh + r * q_st.n + ch * 64 + g * 16 + h * 8)
                                              : make_uint4(0u, 0u, 0u, 0u);
                     const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
+                    if constexpr (Q4) {
+                        // max |Q - qbar| over the valid rows (a missing row would contribute |qbar|)
+                        const float *qm = q_mean + ((size_t)bh * nQblk + qtile) * D + ch * 64 + g * 16 + h * 8;
+                        const float4 ma = *reinterpret_cast<const float4 *>(qm), mb = *reinterpret_cast<const float4 *>(qm + 4);
+                        const float mu[8] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w};
+                        if (r < Nq) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(w[i] & 0xffffu)), fabsf(to_f32<BF16>(w[i] >> 16))));
+                            for (int i = 0; i < 4; ++i)
+                                amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(w[i] & 0xffffu) - mu[2 * i]),
+                                                         fabsf(to_f32<BF16>(w[i] >> 16) - mu[2 * i + 1])));
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(w[i] & 0xffffu)), fabsf(to_f32<BF16>(w[i] >> 16))));
+                    }
                 }
         }
 #pragma unroll
@@ -372,8 +475,65 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
             }
         }
     }
-    const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
+    // (the 4+8 variant converts its scores explicitly: plain INT32 accumulators)
+    constexpr int kInit = Q4 ? 0 : kMagic;
+    const v4i cinit = {kInit, kInit, kInit, kInit};
 
+    // the output scales are fetched now and parked in LDS: the epilogue then waits for no global load
+    if (tid < D / 4)
+        *reinterpret_cast<float4 *>(dv_lds + 4 * tid) = *reinterpret_cast<const float4 *>(dv + (size_t)bhk * D + 4 * tid);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): K^(0) has landed
+    __syncthreads();
+
+    // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
+    float delta_q;
+    if constexpr (QRAW) {
+        float a = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) a = fmaxf(a, q_wave_max[w]);
+        constexpr float kRange = Q4 ? 7.0f : 127.0f;
+        const float rcp = a > 0.0f ? kRange / a : 0.0f;
+        delta_q = a / kRange;
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
+                    float mu[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    if constexpr (Q4) {
+                        const float *qm = q_mean + ((size_t)bh * nQblk + qtile) * D + ch * 64 + g * 16 + h * 8;
+                        const float4 ma = *reinterpret_cast<const float4 *>(qm), mb = *reinterpret_cast<const float4 *>(qm + 4);
+                        mu[0] = ma.x, mu[1] = ma.y, mu[2] = ma.z, mu[3] = ma.w;
+                        mu[4] = mb.x, mu[5] = mb.y, mu[6] = mb.z, mu[7] = mb.w;
+                    }
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        // code = rne(fl(x * rcp)): adding 1.5*2^23 to the (separately rounded) product rounds
+                        // it to the nearest integer, ties to even, and leaves the code's two's-complement
+                        // byte in the low byte of the sum's bit pattern; three byte permutes pack four codes
+                        uint32_t b[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t u = w[2 * hh + (i >> 1)];
+                            float x = to_f32<BF16>((i & 1) ? (u >> 16) : (u & 0xffffu));
+                            if constexpr (Q4) x = x - mu[4 * hh + i];  // one binary32 subtraction, as the quantiser does
+                            float y = x * rcp;
+                            asm volatile("" : "+v"(y));  // keeps the product a rounded binary32 value (no FMA)
+                            b[i] = __builtin_bit_cast(uint32_t, y + kMagicF);
+                        }
+                        const uint32_t lo2 = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+                        const uint32_t hi2 = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+                        qreg[qt][ch][2 * h + hh] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
+                    }
+                }
+    } else {
+        delta_q = dq[(size_t)bh * nQblk + min(row0, Nq - 1) / kBQ];
+    }
+    const double cq = (double)delta_q * (double)sm_scale * 1.4426950408889634;
+
+    // (the accumulators start their life here, after the prologue, whose Q registers they reuse)
     float m[NQ], l[NQ], alpha[NQ];
     v4f o[CT][NQ];
     v4i s[NQ][8];
@@ -390,50 +550,6 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
         pb[qt] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
-    // the output scales are fetched now and parked in LDS: the epilogue then waits for no global load
-    if (tid < D / 4)
-        *reinterpret_cast<float4 *>(dv_lds + 4 * tid) = *reinterpret_cast<const float4 *>(dv + (size_t)bhk * D + 4 * tid);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): K^(0) has landed
-    __syncthreads();
-
-    // de-quantisation constant of this wave's query block (its 16*NQ rows lie inside one Q block)
-    float delta_q;
-    if constexpr (QRAW) {
-        float a = 0.0f;
-#pragma unroll
-        for (int w = 0; w < NWAVE; ++w) a = fmaxf(a, q_wave_max[w]);
-        const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
-        delta_q = a / 127.0f;
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-            for (int ch = 0; ch < KC; ++ch)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const uint32_t w[4] = {qraw[qt][ch][h].x, qraw[qt][ch][h].y, qraw[qt][ch][h].z, qraw[qt][ch][h].w};
-#pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        // code = rne(fl(x * rcp)): adding 1.5*2^23 to the (separately rounded) product rounds
-                        // it to the nearest integer, ties to even, and leaves the code's two's-complement
-                        // byte in the low byte of the sum's bit pattern; three byte permutes pack four codes
-                        uint32_t b[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const uint32_t u = w[2 * hh + (i >> 1)];
-                            const float x = to_f32<BF16>((i & 1) ? (u >> 16) : (u & 0xffffu));
-                            float y = x * rcp;
-                            asm volatile("" : "+v"(y));  // keeps the product a rounded binary32 value (no FMA)
-                            b[i] = __builtin_bit_cast(uint32_t, y + kMagicF);
-                        }
-                        const uint32_t lo2 = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-                        const uint32_t hi2 = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
-                        qreg[qt][ch][2 * h + hh] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
-                    }
-                }
-    } else {
-        delta_q = dq[(size_t)bh * nQblk + min(row0, Nq - 1) / kBQ];
-    }
-    const double cq = (double)delta_q * (double)sm_scale * 1.4426950408889634;
 
     // piece k of the copy this group makes during its matrix slot M(j): K^(j+1) (first group), V^(j) (second)
     auto copy_k = [&](int j) {
@@ -441,6 +557,7 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 #pragma unroll
             for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[(j + 1) & 1], Kh, k_bytes, c_voff, wig, k, j + 1);
         }
+        copy_ds(j + 1);
     };
     auto copy_v = [&](int j) {
         if (j < nsteps) {
@@ -520,11 +637,19 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
                 const int lim_max = CAUSAL ? min(Nk - 1, row0 + qt * 16 + 15 + shift) : Nk - 1;
                 const int t_lo = min(8, max(0, (lim_min - key0 + 1) >> 4));
                 const int t_hi = min(8, max(0, ((lim_max - key0) >> 4) + 1));
-                alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
-                                               key0 + 4 * g, lim, t_lo, t_hi);
+                if constexpr (Q4)
+                    alpha[qt] = softmax_step_q4<true>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim, t_lo,
+                                                      t_hi, reinterpret_cast<const float4 *>(&ds_lds[j % 3][32 * g]));
+                else
+                    alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
+                                                   key0 + 4 * g, lim, t_lo, t_hi);
             } else {
-                alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0, 8,
-                                                8);
+                if constexpr (Q4)
+                    alpha[qt] = softmax_step_q4<false>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], 0, 0, 8, 8,
+                                                       reinterpret_cast<const float4 *>(&ds_lds[j % 3][32 * g]));
+                else
+                    alpha[qt] = softmax_step<false>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt], 0, 0,
+                                                    8, 8);
             }
         }
         __builtin_amdgcn_s_setprio(0);
@@ -580,19 +705,22 @@ __global__ __launch_bounds__(NWAVE * 64, WPS) void attn_kernel(
 template <int D, int NQ, int NWAVE, int WPS>
 hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                     const float *k_scale, const float *v_scale, void *out, Strides o_st, int B, int Hq, int Hkv, int Nq,
-                    int Nk, bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream) {
+                    int Nk, bool causal, float sm_scale, float log2_pr, bool bf16_out, hipStream_t stream,
+                    const float *q_mean, const float *dsx) {
     constexpr int BM = 16 * NQ * NWAVE;
     const int BH = B * Hq;
     const dim3 grid(BH * cdiv(Nq, BM));  // (at most 65535 * 32768 < 2^31 workgroups)
     const int nT = cdiv(Nk, kW), nQ = cdiv(Nq, kBQ), nK = cdiv(Nk, kBK);
     uint16_t *o16 = static_cast<uint16_t *>(out);
-#define SAGE_LAUNCH(C, BF, QR)                                                                              \
-    attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR><<<grid, NWAVE * 64, 0, stream>>>(q, k_i8, v_fp8, q_scale, k_scale, \
-                                                                             v_scale, o16, q_st, o_st, Nq, Nk,  \
-                                                                             nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
-                                                                             log2_pr, cdiv(Nq, BM))
-#define SAGE_LAUNCH_Q(C, BF) \
-    if (q_raw) SAGE_LAUNCH(C, BF, true); else SAGE_LAUNCH(C, BF, false)
+    const bool q4 = dsx != nullptr;  // the 4+8 variant (always with unquantised Q)
+#define SAGE_LAUNCH(C, BF, QR, F4)                                                                               \
+    attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR, F4><<<grid, NWAVE * 64, 0, stream>>>(                                \
+        q, k_i8, v_fp8, q_scale, k_scale, v_scale, o16, q_st, o_st, Nq, Nk, nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
+        log2_pr, cdiv(Nq, BM), q_mean, dsx)
+#define SAGE_LAUNCH_Q(C, BF)                                   \
+    if (q4) SAGE_LAUNCH(C, BF, true, true);                    \
+    else if (q_raw) SAGE_LAUNCH(C, BF, true, false);           \
+    else SAGE_LAUNCH(C, BF, false, false)
     if (causal) {
         if (bf16_out) { SAGE_LAUNCH_Q(true, true); } else { SAGE_LAUNCH_Q(true, false); }
     } else {
@@ -608,16 +736,16 @@ hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8,
 hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8,
                        const float *q_scale, const float *k_scale, const float *v_scale, void *out, Strides o_st, int B,
                        int Hq, int Hkv, int Nq, int Nk, int d, bool causal, float sm_scale, float p_r, bool bf16_out,
-                       hipStream_t stream) {
+                       hipStream_t stream, const float *q_mean, const float *dsx) {
     const float log2_pr = (float)log2((double)p_r);
     // 16 query rows per wavefront, 8 wavefronts (128 rows) per workgroup, 4 wavefronts per SIMD:
     // the fastest of the measured shapes for both head dimensions (the kernel is bound by vector
     // ALU issue, and more resident wavefronts overlap MFMA and VALU work better than wider tiles)
     if (d == 128)
         return launch_d<128, 1, 8, 4>(q, q_raw, q_st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, o_st, B, Hq, Hkv, Nq, Nk,
-                                      causal, sm_scale, log2_pr, bf16_out, stream);
+                                      causal, sm_scale, log2_pr, bf16_out, stream, q_mean, dsx);
     return launch_d<64, 1, 8, 4>(q, q_raw, q_st, k_i8, v_fp8, q_scale, k_scale, v_scale, out, o_st, B, Hq, Hkv, Nq, Nk, causal,
-                                 sm_scale, log2_pr, bf16_out, stream);
+                                 sm_scale, log2_pr, bf16_out, stream, q_mean, dsx);
 }
 
 }  // namespace sage

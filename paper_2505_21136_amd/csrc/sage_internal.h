@@ -42,17 +42,30 @@ hipError_t launch_quant_v(const void *v, Strides v_st, uint8_t *v_fp8, float *v_
                           int d, bool bf16, hipStream_t stream, const QuantScratch &ws);
 
 // K and V of the same shape together: three launches instead of six, identical results
+// (int4: the K codes of the 4+8 variant, range [-7, 7], one per byte)
 hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v_st, int8_t *k_i8, float *k_scale,
                            float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
-                           bool bf16, hipStream_t stream, const QuantScratch &ws);
+                           bool bf16, hipStream_t stream, const QuantScratch &ws, bool int4 = false);
+
+// 4+8 variant.  Block means of Q ([B,H,ceil(N/kBQ),d]); with q_i4 != NULL also the stand-alone INT4 codes and
+// scales of Q minus its block means.
+hipError_t launch_quant_q4(const void *q, Strides q_st, float *q_mean, int8_t *q_i4, float *q_scale, int B, int H, int N,
+                           int d, bool bf16, hipStream_t stream);
+// The score correction qbar K'^T in exponent units, [B*Hq][ceil(Nq/kBQ)][ceil(Nk/kW)][128] floats in the attention
+// kernel's lane order (see delta_s_kernel).
+hipError_t launch_delta_s(const void *k, Strides k_st, const float *k_mean, const float *q_mean, float *dsx, int B,
+                          int Hq, int Hkv, int Nq, int Nk, int d, bool causal, float sm_scale, bool bf16,
+                          hipStream_t stream);
 
 // stage 2 launch (sage_attn.hip): Hq query heads over Hkv K/V heads, Nq query rows over Nk keys.
 // q_raw = false: q is Q^ (int8) with scales q_scale; q_raw = true: q is the unquantised 16-bit Q
 // (type of the output), quantised inside the kernel, q_scale unused.  q and out are addressed
 // through their strides; K^, V^ and the scales are contiguous.
+// dsx != NULL selects the 4+8 variant: q is the unquantised Q, k_i8 holds INT4 codes, q_mean the block means of Q
+// (launch_quant_q4) and dsx the score correction (launch_delta_s).
 hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                        const float *k_scale, const float *v_scale, void *out, Strides o_st, int B, int Hq, int Hkv,
                        int Nq, int Nk, int d, bool causal, float sm_scale, float p_r, bool bf16_out,
-                       hipStream_t stream);
+                       hipStream_t stream, const float *q_mean = nullptr, const float *dsx = nullptr);
 
 }  // namespace sage

@@ -191,11 +191,14 @@ __global__ __launch_bounds__(1024) void finalize_kv_kernel(const double *__restr
 }
 
 // ---------------------------------------------------------------------------
-// Per-block INT8 quantisation (Sec. 2.1): one workgroup per block of BLOCK
+// Per-block integer quantisation (Sec. 2.1): one workgroup per block of BLOCK
 // tokens, the block lives in registers between the max pass and the code pass.
-// 256 threads; wmax: four floats of LDS.
+// QMAX = 127: INT8 codes; QMAX = 7: the INT4 codes of the 4+8 variant (one per
+// byte).  SMOOTH = 0: no mean is subtracted; 1: `mean` holds one vector per
+// head (K smoothing, Sec. 3); 2: one vector per head and block (Q smoothing of
+// the 4+8 variant).  256 threads; wmax: four floats of LDS.
 // ---------------------------------------------------------------------------
-template <bool BF16, int D, int BLOCK, bool SMOOTH>
+template <bool BF16, int D, int BLOCK, int SMOOTH, int QMAX>
 __device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, Strides st, int H,
                                                 const float *__restrict__ mean, int8_t *__restrict__ codes,
                                                 float *__restrict__ scale, int N, int nblk, float *wmax, int bh,
@@ -203,14 +206,16 @@ __device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, 
     constexpr int LPR = D / 8;
     constexpr int RP = 256 / LPR;
     constexpr int ITER = BLOCK / RP;
+    constexpr float kRange = (float)QMAX;
     static_assert(BLOCK % RP == 0, "block must be a multiple of the rows covered per pass");
 
     const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
     const uint16_t *Xh = X + (bh / H) * st.b + (bh % H) * st.h;
 
     float mu[8];
+    const size_t mrow = SMOOTH == 2 ? (size_t)bh * nblk + blk : (size_t)bh;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) mu[j] = SMOOTH ? mean[(size_t)bh * D + co * 8 + j] : 0.0f;
+    for (int j = 0; j < 8; ++j) mu[j] = SMOOTH ? mean[mrow * D + co * 8 + j] : 0.0f;
 
     float x[ITER][8];
     float amax = 0.0f;
@@ -222,7 +227,7 @@ __device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, 
             unpack8<BF16>(u, x[it]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if constexpr (SMOOTH) x[it][j] = x[it][j] - mu[j];
+                if constexpr (SMOOTH != 0) x[it][j] = x[it][j] - mu[j];
                 amax = fmaxf(amax, fabsf(x[it][j]));
             }
         } else {
@@ -235,8 +240,8 @@ __device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, 
     if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = amax;
     __syncthreads();
     const float a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
-    const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
-    if (threadIdx.x == 0) scale[(size_t)bh * nblk + blk] = a / 127.0f;
+    const float rcp = a > 0.0f ? kRange / a : 0.0f;
+    if (threadIdx.x == 0) scale[(size_t)bh * nblk + blk] = a / kRange;
 
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
@@ -249,6 +254,115 @@ __device__ __forceinline__ void quant_int8_body(const uint16_t *__restrict__ X, 
                 w[j >> 2] |= ((uint32_t)c & 0xffu) << (8 * (j & 3));
             }
             *reinterpret_cast<uint2 *>(codes + ((size_t)bh * N + r) * D + co * 8) = make_uint2(w[0], w[1]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 4+8 variant: what smoothing of Q subtracts (Sec. 3 names the step; reading: the mean of each Q block,
+// per channel, over the block's valid tokens).  mean[bh][blk][c] = float(sum_r Q[r][c] / rows), the sum in
+// double (exact for 16-bit inputs, so the order of the additions does not matter).  One workgroup of 256
+// threads per Q block; sm: RP x D doubles.
+// ---------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t *__restrict__ Q, Strides st, int H, int N,
+                                                         int nblk, float *__restrict__ mean) {
+    constexpr int LPR = D / 8;
+    constexpr int RP = 256 / LPR;
+    __shared__ double sm[RP][D];
+    const int bh = blockIdx.y, blk = blockIdx.x;
+    const int co = threadIdx.x % LPR, rr = threadIdx.x / LPR;
+    const uint16_t *Qh = Q + (bh / H) * st.b + (bh % H) * st.h;
+    const int r0 = blk * kBQ, r1 = min(r0 + kBQ, N);
+    double acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+    for (int r = r0 + rr; r < r1; r += RP) {
+        float f[8];
+        unpack8<BF16>(*reinterpret_cast<const uint4 *>(Qh + r * st.n + co * 8), f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (double)f[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[rr][co * 8 + j] = acc[j];
+    __syncthreads();
+    if (threadIdx.x < D) {
+        double a = sm[0][threadIdx.x];
+        for (int i = 1; i < RP; ++i) a += sm[i][threadIdx.x];
+        mean[((size_t)bh * nblk + blk) * D + threadIdx.x] = (float)(a / (double)(r1 - r0));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 4+8 variant: the score correction.  With Q' = Q - qbar_i on Q block i, Q K'^T = Q' K'^T + qbar_i K'^T; the
+// second term, dS[i][n] = sum_c qbar[i][c] * K'[n][c] with the smoothed UNquantised keys K' = K - mu_K, is
+// computed here in FP32 and stored in the units of the softmax exponent (times sm_scale * log2 e), in the key
+// order in which a lane of the attention kernel holds its scores: [B*Hq][nQ][nT][128] floats, position
+// 32*g + 4*t + i of a tile = key 16*t + 4*g + i (t < 8, g < 4, i < 4).  Keys >= Nk hold 0.
+// One workgroup of 128 threads per 128-key tile and K/V head; a thread owns one key and keeps its K' row in
+// registers; the block means of 16 Q blocks at a time are staged in LDS and read as broadcasts.
+// Causal launches skip the Q blocks that see no key of the tile.
+// ---------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(128) void delta_s_kernel(const uint16_t *__restrict__ K, Strides k_st, int Hkv,
+                                                      const float *__restrict__ k_mean,
+                                                      const float *__restrict__ q_mean, float *__restrict__ dsx,
+                                                      int Hq, int Nq, int Nk, int nQ, int nT, float sm_log2e,
+                                                      int causal) {
+    constexpr int QB = 32;  // Q blocks per LDS stage
+    __shared__ __attribute__((aligned(16))) float qm[QB][D];
+    const int T = blockIdx.x, bhk = blockIdx.y;
+    const int group = Hq / Hkv;
+    const int n = T * 128 + threadIdx.x;
+    float kp[D];
+    {
+        const uint16_t *Kh = K + (bhk / Hkv) * k_st.b + (bhk % Hkv) * k_st.h;
+#pragma unroll
+        for (int c8 = 0; c8 < D / 8; ++c8) {
+            float f[8];
+            if (n < Nk) {
+                unpack8<BF16>(*reinterpret_cast<const uint4 *>(Kh + n * k_st.n + c8 * 8), f);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) f[j] = 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) kp[c8 * 8 + j] = n < Nk ? f[j] - k_mean[(size_t)bhk * D + c8 * 8 + j] : 0.0f;
+        }
+    }
+    // position of this key inside its tile in the attention kernel's lane order
+    const int kt = threadIdx.x;
+    const int pos = 32 * ((kt >> 2) & 3) + 4 * (kt >> 4) + (kt & 3);
+    // causal (mask aligned to the end of both sequences): Q block i sees key n iff n <= i*kBQ + kBQ-1 + Nk - Nq
+    int i_first = 0;
+    if (causal) i_first = max(0, (T * 128 - (Nk - Nq)) / kBQ);
+    for (int hq = 0; hq < group; ++hq) {
+        const int bhq = (bhk / Hkv) * Hq + (bhk % Hkv) * group + hq;
+        for (int i0 = i_first - i_first % QB; i0 < nQ; i0 += QB) {
+            __syncthreads();
+            for (int e = threadIdx.x; e < QB * D / 4; e += 128) {
+                const int i = i0 + e / (D / 4);
+                const float4 v = i < nQ ? *reinterpret_cast<const float4 *>(q_mean + ((size_t)bhq * nQ + i) * D + 4 * (e % (D / 4)))
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                *reinterpret_cast<float4 *>(&qm[e / (D / 4)][4 * (e % (D / 4))]) = v;
+            }
+            __syncthreads();
+            // one Q block at a time (a rolled loop: the key's row stays in registers, the block's means are
+            // broadcast reads at constant offsets), four partial sums
+#pragma unroll 1
+            for (int i = 0; i < QB; ++i) {
+                if (i0 + i >= nQ) break;
+                float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll
+                for (int c4 = 0; c4 < D / 4; ++c4) {
+                    const float4 m = *reinterpret_cast<const float4 *>(&qm[i][4 * c4]);
+                    a0 = __builtin_fmaf(m.x, kp[4 * c4], a0);
+                    a1 = __builtin_fmaf(m.y, kp[4 * c4 + 1], a1);
+                    a2 = __builtin_fmaf(m.z, kp[4 * c4 + 2], a2);
+                    a3 = __builtin_fmaf(m.w, kp[4 * c4 + 3], a3);
+                }
+                dsx[(((size_t)bhq * nQ + i0 + i) * nT + T) * 128 + pos] = ((a0 + a1) + (a2 + a3)) * sm_log2e;
+            }
         }
     }
 }
@@ -307,12 +421,12 @@ __device__ __forceinline__ void quant_v_body(const uint16_t *__restrict__ V, Str
 }
 
 // grid (blocks, B*H)
-template <bool BF16, int D, int BLOCK, bool SMOOTH>
+template <bool BF16, int D, int BLOCK, int SMOOTH, int QMAX>
 __global__ __launch_bounds__(256) void quant_int8_kernel(const uint16_t *__restrict__ X, Strides st, int H,
                                                          const float *__restrict__ mean, int8_t *__restrict__ codes,
                                                          float *__restrict__ scale, int N, int nblk) {
     __shared__ float wmax[4];
-    quant_int8_body<BF16, D, BLOCK, SMOOTH>(X, st, H, mean, codes, scale, N, nblk, wmax, blockIdx.y, blockIdx.x);
+    quant_int8_body<BF16, D, BLOCK, SMOOTH, QMAX>(X, st, H, mean, codes, scale, N, nblk, wmax, blockIdx.y, blockIdx.x);
 }
 
 // grid (tiles, B*H)
@@ -325,7 +439,7 @@ __global__ __launch_bounds__(256) void quant_v_kernel(const uint16_t *__restrict
 }
 
 // K blocks (blockIdx.x < nK) and V tiles (the rest) in one launch: grid (nK + nT, B*H)
-template <bool BF16, int D>
+template <bool BF16, int D, int QMAX>
 __global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restrict__ K, Strides k_st,
                                                        const float *__restrict__ mean, int8_t *__restrict__ k_codes,
                                                        float *__restrict__ k_scale, int nK,
@@ -335,8 +449,8 @@ __global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restric
     __shared__ uint32_t tile[D * 32];
     const int x = blockIdx.x;  // (workgroup-uniform branch)
     if (x < nK)
-        quant_int8_body<BF16, D, kBK, true>(K, k_st, H, mean, k_codes, k_scale, N, nK, reinterpret_cast<float *>(tile),
-                                            blockIdx.y, x);
+        quant_int8_body<BF16, D, kBK, 1, QMAX>(K, k_st, H, mean, k_codes, k_scale, N, nK,
+                                               reinterpret_cast<float *>(tile), blockIdx.y, x);
     else
         quant_v_body<BF16, D>(V, v_st, H, v_rcp, Vt, N, nT, tile, blockIdx.y, x - nK);
 }
@@ -347,7 +461,7 @@ template <bool BF16, int D>
 hipError_t quant_q_impl(const uint16_t *q, Strides st, int8_t *q_i8, float *q_scale, int BH, int H, int N,
                         hipStream_t stream) {
     const int nQ = cdiv(N, kBQ);
-    quant_int8_kernel<BF16, D, kBQ, false><<<dim3(nQ, BH), 256, 0, stream>>>(q, st, H, nullptr, q_i8, q_scale, N, nQ);
+    quant_int8_kernel<BF16, D, kBQ, 0, 127><<<dim3(nQ, BH), 256, 0, stream>>>(q, st, H, nullptr, q_i8, q_scale, N, nQ);
     return hipGetLastError();
 }
 
@@ -359,7 +473,7 @@ hipError_t quant_k_impl(const uint16_t *k, Strides st, int8_t *k_i8, float *k_sc
     colstats_kernel<BF16, D, false><<<dim3(chunks, BH), 256, 0, stream>>>(k, st, H, N, chunks, ws.k_sum_part, nullptr);
     finalize_mean_kernel<<<BH, 1024, 0, stream>>>(ws.k_sum_part, chunks, N, D, k_mean);
     // K right after its statistics pass: its second read can still be served by the last-level cache
-    quant_int8_kernel<BF16, D, kBK, true><<<dim3(nK, BH), 256, 0, stream>>>(k, st, H, k_mean, k_i8, k_scale, N, nK);
+    quant_int8_kernel<BF16, D, kBK, 1, 127><<<dim3(nK, BH), 256, 0, stream>>>(k, st, H, k_mean, k_i8, k_scale, N, nK);
     return hipGetLastError();
 }
 
@@ -375,7 +489,7 @@ hipError_t quant_v_impl(const uint16_t *v, Strides st, uint8_t *v_fp8, float *v_
 }
 
 // K and V of one shape in three launches instead of six (same kernels' bodies, same results)
-template <bool BF16, int D>
+template <bool BF16, int D, int QMAX>
 hipError_t quant_kv_impl(const uint16_t *k, Strides k_st, const uint16_t *v, Strides v_st, int8_t *k_i8, float *k_scale,
                          float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int BH, int H, int N,
                          hipStream_t stream, const QuantScratch &ws) {
@@ -385,8 +499,19 @@ hipError_t quant_kv_impl(const uint16_t *k, Strides k_st, const uint16_t *v, Str
                                                                          ws.v_max_part);
     finalize_kv_kernel<<<dim3(BH, 2), 1024, 0, stream>>>(ws.k_sum_part, ws.v_max_part, chunks, N, D, v_r, k_mean,
                                                          v_scale, ws.v_rcp);
-    quant_kv_kernel<BF16, D><<<dim3(nK + nT, BH), 256, 0, stream>>>(k, k_st, k_mean, k_i8, k_scale, nK, v, v_st, ws.v_rcp,
-                                                                    v_fp8, nT, H, N);
+    quant_kv_kernel<BF16, D, QMAX><<<dim3(nK + nT, BH), 256, 0, stream>>>(k, k_st, k_mean, k_i8, k_scale, nK, v, v_st,
+                                                                          ws.v_rcp, v_fp8, nT, H, N);
+    return hipGetLastError();
+}
+
+// 4+8 variant, Q side: block means, and (stand-alone) the INT4 codes of Q minus its block means
+template <bool BF16, int D>
+hipError_t q4_impl(const uint16_t *q, Strides st, float *q_mean, int8_t *q_i4, float *q_scale, int BH, int H, int N,
+                   hipStream_t stream) {
+    const int nQ = cdiv(N, kBQ);
+    block_mean_kernel<BF16, D><<<dim3(nQ, BH), 256, 0, stream>>>(q, st, H, N, nQ, q_mean);
+    if (q_i4)
+        quant_int8_kernel<BF16, D, kBQ, 2, 7><<<dim3(nQ, BH), 256, 0, stream>>>(q, st, H, q_mean, q_i4, q_scale, N, nQ);
     return hipGetLastError();
 }
 
@@ -444,14 +569,48 @@ hipError_t launch_quant_v(const void *v, Strides st, uint8_t *v_fp8, float *v_sc
 
 hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v_st, int8_t *k_i8, float *k_scale,
                            float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
-                           bool bf16, hipStream_t stream, const QuantScratch &ws) {
+                           bool bf16, hipStream_t stream, const QuantScratch &ws, bool int4) {
     const uint16_t *k16 = static_cast<const uint16_t *>(k), *v16 = static_cast<const uint16_t *>(v);
     const int BH = B * H;
-#define SAGE_KV(BF, DD) \
-    quant_kv_impl<BF, DD>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
-    if (d == 128) return bf16 ? SAGE_KV(true, 128) : SAGE_KV(false, 128);
-    return bf16 ? SAGE_KV(true, 64) : SAGE_KV(false, 64);
+#define SAGE_KV(BF, DD, QM) \
+    quant_kv_impl<BF, DD, QM>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
+    if (int4) {
+        if (d == 128) return bf16 ? SAGE_KV(true, 128, 7) : SAGE_KV(false, 128, 7);
+        return bf16 ? SAGE_KV(true, 64, 7) : SAGE_KV(false, 64, 7);
+    }
+    if (d == 128) return bf16 ? SAGE_KV(true, 128, 127) : SAGE_KV(false, 128, 127);
+    return bf16 ? SAGE_KV(true, 64, 127) : SAGE_KV(false, 64, 127);
 #undef SAGE_KV
+}
+
+hipError_t launch_quant_q4(const void *q, Strides st, float *q_mean, int8_t *q_i4, float *q_scale, int B, int H, int N,
+                           int d, bool bf16, hipStream_t stream) {
+    const uint16_t *q16 = static_cast<const uint16_t *>(q);
+    const int BH = B * H;
+    if (d == 128)
+        return bf16 ? q4_impl<true, 128>(q16, st, q_mean, q_i4, q_scale, BH, H, N, stream)
+                    : q4_impl<false, 128>(q16, st, q_mean, q_i4, q_scale, BH, H, N, stream);
+    return bf16 ? q4_impl<true, 64>(q16, st, q_mean, q_i4, q_scale, BH, H, N, stream)
+                : q4_impl<false, 64>(q16, st, q_mean, q_i4, q_scale, BH, H, N, stream);
+}
+
+hipError_t launch_delta_s(const void *k, Strides k_st, const float *k_mean, const float *q_mean, float *dsx, int B,
+                          int Hq, int Hkv, int Nq, int Nk, int d, bool causal, float sm_scale, bool bf16,
+                          hipStream_t stream) {
+    const uint16_t *k16 = static_cast<const uint16_t *>(k);
+    const dim3 grid(cdiv(Nk, kW), B * Hkv);
+    const int nQ = cdiv(Nq, kBQ), nT = cdiv(Nk, kW);
+    const float sm_log2e = (float)((double)sm_scale * 1.4426950408889634);
+#define SAGE_DS(BF, DD) \
+    delta_s_kernel<BF, DD><<<grid, 128, 0, stream>>>(k16, k_st, Hkv, k_mean, q_mean, dsx, Hq, Nq, Nk, nQ, nT, sm_log2e, \
+                                                     causal ? 1 : 0)
+    if (d == 128) {
+        if (bf16) SAGE_DS(true, 128); else SAGE_DS(false, 128);
+    } else {
+        if (bf16) SAGE_DS(true, 64); else SAGE_DS(false, 64);
+    }
+#undef SAGE_DS
+    return hipGetLastError();
 }
 
 }  // namespace sage

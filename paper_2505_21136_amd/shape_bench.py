@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
 """Time the whole forward pass (sage_attn_fwd_gqa: K/V quantisation + attention with Q quantised in its
-prologue) on shapes the five benchmark workloads do not cover: grouped-query prefill, rectangular
+prologue; with --four-bit the 4+8 variant, sage_attn_fwd_4bit) on shapes the five benchmark workloads do not cover: grouped-query prefill, rectangular
 (N_q != N_k) and decode-shaped calls.
 
     python -m paper_2505_21136_amd.shape_bench --shape B,Hq,Hkv,Nq,Nk,d[,causal[,fp16|bf16]] [--shape ...]
@@ -25,7 +25,7 @@ def visible_pairs(nq: int, nk: int, causal: bool) -> float:
     return float(nq) * (nk - nq) + nq * (nq + 1) / 2.0
 
 
-def run(shape: str, steps: int, warm_s: float) -> dict:
+def run(shape: str, steps: int, warm_s: float, four_bit: bool = False) -> dict:
     f = shape.split(",")
     B, Hq, Hkv, Nq, Nk, d = (int(x) for x in f[:6])
     causal = bool(int(f[6])) if len(f) > 6 else False
@@ -36,10 +36,14 @@ def run(shape: str, steps: int, warm_s: float) -> dict:
          + 3.0 * torch.randn((B, Hkv, 1, d), generator=g, device="cuda")).to(dtype)
     v = torch.randn((B, Hkv, Nk, d), generator=g, device="cuda").to(dtype)
     out = torch.empty_like(q)
-    ws = torch.empty(sage.workspace_bytes_gqa(B, Hq, Hkv, Nq, Nk, d), dtype=torch.uint8, device="cuda")
+    nbytes = (sage.workspace_bytes_4bit if four_bit else sage.workspace_bytes_gqa)(B, Hq, Hkv, Nq, Nk, d)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
 
     def call():
-        sage.sage_attn_fwd_gqa(q, k, v, causal=causal, out=out, workspace=ws)
+        if four_bit:
+            sage.sage_attn_fwd_4bit(q, k, v, causal=causal, out=out, workspace=ws)
+        else:
+            sage.sage_attn_fwd_gqa(q, k, v, causal=causal, out=out, workspace=ws)
 
     call()
     torch.cuda.synchronize()
@@ -57,7 +61,7 @@ def run(shape: str, steps: int, warm_s: float) -> dict:
     b.synchronize()
     ms = a.elapsed_time(b) / steps
     ops = 4.0 * B * Hq * visible_pairs(Nq, Nk, causal) * d
-    return {"shape": dict(B=B, Hq=Hq, Hkv=Hkv, Nq=Nq, Nk=Nk, d=d, causal=causal, dtype=str(dtype).split(".")[-1]),
+    return {"variant": "4+8" if four_bit else "8+8", "shape": dict(B=B, Hq=Hq, Hkv=Hkv, Nq=Nq, Nk=Nk, d=d, causal=causal, dtype=str(dtype).split(".")[-1]),
             "ms_per_call": round(ms, 4), "attention_TOPS": round(ops / (ms * 1e-3) / 1e12, 2),
             "workgroups": B * Hq * -(-Nq // 128)}
 
@@ -65,6 +69,7 @@ def run(shape: str, steps: int, warm_s: float) -> dict:
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--shape", action="append", required=True)
+    ap.add_argument("--four-bit", action="store_true", help="time sage_attn_fwd_4bit (the 4+8 variant) instead")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warm-seconds", type=float, default=0.15)
     args = ap.parse_args()
@@ -72,7 +77,7 @@ def main():
         print("no GPU visible; there is no CPU fallback", file=sys.stderr)
         sys.exit(2)
     for s in args.shape:
-        print(json.dumps(run(s, args.steps, args.warm_seconds)), flush=True)
+        print(json.dumps(run(s, args.steps, args.warm_seconds, args.four_bit)), flush=True)
 
 
 if __name__ == "__main__":

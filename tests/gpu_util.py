@@ -75,12 +75,12 @@ def oracle_rows(wq, b, h, row0, row1, *, causal, sm_scale, out_dtype, p_r=224.0)
                             out_dtype=out_dtype)
 
 
-def assert_parity(ref, got, dtype, what=""):
+def assert_parity(ref, got, dtype, what="", flip_factor=1.0):
     """The parity gate (tests/parity_gate.py): the two norms of the benchmark definition over the whole block
     plus the worst single row, the largest element-wise difference and the fraction beyond one 16-bit ulp."""
     m = parity_metrics(ref, got, dtype)
     say(f"   {what}: {format_metrics(m)}")
     record_metrics(what, m)
-    bad = parity_failures(m)
+    bad = parity_failures(m, flip_factor)
     assert not bad, f"{what}: " + "; ".join(bad)
     return m["cos"], m["rel_l1"]

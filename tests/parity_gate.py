@@ -96,8 +96,12 @@ def parity_metrics(ref, got, dtype: str) -> dict:
     )
 
 
-def parity_failures(m: dict) -> list:
-    """Names of the limits the metrics `m` break (empty list: the gate passes)."""
+def parity_failures(m: dict, flip_factor: float = 1.0) -> list:
+    """Names of the limits the metrics `m` break (empty list: the gate passes).
+
+    flip_factor scales the two limits that count flipped decisions (`beyond`, `differ`): a path whose exponent
+    carries more FP32 evaluation error flips proportionally more FP8 roundings.  The 4+8 variant, whose score
+    correction is an FP32 dot product of d terms, is gated with 2 (measured: 1.6 to 2.1 times the 8+8 counts)."""
     bad = []
     if not m["finite"]:
         bad.append("non-finite output")
@@ -109,11 +113,11 @@ def parity_failures(m: dict) -> list:
         bad.append(f"row {m['row_argmax']}: relL1 {m['row_l1']:.3e} > {ROW_L1_MAX}")
     if not m["max_abs"] <= MAX_ABS_MAX:
         bad.append(f"max |diff| / rms {m['max_abs']:.3e} > {MAX_ABS_MAX}")
-    allowed = max(BEYOND_ULP_MIN_COUNT, math.ceil(BEYOND_ULP_MAX[m["dtype"]] * m["n"]))
+    allowed = max(BEYOND_ULP_MIN_COUNT, math.ceil(flip_factor * BEYOND_ULP_MAX[m["dtype"]] * m["n"]))
     if m["beyond_count"] > allowed:
         bad.append(f"{m['beyond_count']} of {m['n']} elements beyond one ulp (allowed {allowed})")
-    if m["differ"] * m["n"] > max(DIFFER_MIN_COUNT, DIFFER_MAX[m["dtype"]] * m["n"]):
-        bad.append(f"{m['differ']:.3f} of the elements differ (allowed {DIFFER_MAX[m['dtype']]})")
+    if m["differ"] * m["n"] > max(DIFFER_MIN_COUNT, flip_factor * DIFFER_MAX[m["dtype"]] * m["n"]):
+        bad.append(f"{m['differ']:.3f} of the elements differ (allowed {flip_factor * DIFFER_MAX[m['dtype']]})")
     return bad
 
 
