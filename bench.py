@@ -35,10 +35,14 @@ PEAK_HBM = 8.0e12            # B/s
 # the kernel's SIMD time.
 PROFILED = {
     "cfg5": dict(source="profiles/attn_kernel_cfg5_counters.md",
-                 traffic=int(885116 * 1024 * 2.0 + 196608 * 1024 * 1.0),
-                 valu_per_step=230.3, mfma_i8=16, mfma_f8=8, half_rate=49.2, valu_busy=0.91, mfma_busy=0.41),
+                 traffic=int(885132 * 1024 * 2.0 + 196608 * 1024 * 1.0),
+                 valu_per_step=222.2, mfma_i8=16, mfma_f8=8, half_rate=49.2, valu_busy=0.88, mfma_busy=0.41),
     "cfg3": dict(source="profiles/attn_kernel_cfg5_counters.md (section cfg3)", traffic=None,
-                 valu_per_step=218.6, mfma_i8=8, mfma_f8=4, half_rate=49.2, valu_busy=0.99, mfma_busy=0.23),
+                 valu_per_step=211.7, mfma_i8=8, mfma_f8=4, half_rate=49.2, valu_busy=0.98, mfma_busy=0.24),
+    # causal: per executed wavefront-step, prologue and epilogue of the short workgroups included
+    "cfg2": dict(source="profiles/attn_kernel_cfg5_counters.md (section cfg2)",
+                 traffic=int(174437 * 1024 * 2.0 + 131182 * 1024 * 1.0),
+                 valu_per_step=266.9, mfma_i8=16, mfma_f8=8, half_rate=49.0, valu_busy=0.80, mfma_busy=0.32),
 }
 
 
