@@ -143,15 +143,15 @@ int sage_quant_kv(const void *k, const void *v, int8_t *k_i8, float *k_scale, fl
 /*
  * sage_quant_kv for callers that cannot allocate and have no workspace to hand over: code recorded
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
- * outputs bit for bit; the scratch (partial column statistics, about 12 bytes per channel and 1024 tokens
- * of every head) lives in a static device array inside the library, SAGE_STATIC_SCRATCH_BYTES (8 MiB)
+ * outputs bit for bit; the scratch (partial column statistics, 12 bytes per channel and per 256 tokens
+ * (d = 128) or 512 tokens (d = 64) of every head) lives in a static device array inside the library, SAGE_STATIC_SCRATCH_BYTES (8 MiB)
  * per GPU, which each GPU the library runs on holds until the process ends.  The call allocates nothing
  * and frees nothing; on its first use on a device it looks up that device's copy of the array (the
  * device must be current, as for every call).  Arguments as for sage_quant_kv, without the workspace.
  *   returns SAGE_ESCRATCH when sage_quant_workspace_bytes(B,H,N,d) > SAGE_STATIC_SCRATCH_BYTES
  *           (nothing is enqueued; use sage_quant_kv), otherwise as sage_quant_kv.
- * All calls on one GPU share that GPU's array: the scratch keeps the last call's contents (nothing in it
- * has to start at zero, every value read is written earlier in the same call), and two calls that
+ * All calls on one GPU share that GPU's array: the scratch keeps the last call's contents (what has to
+ * start at zero is cleared by a fill kernel of the same call, everything else is written before it is read), and two calls that
  * overlap on one GPU -- different streams, or different threads -- race on it.  Calls on one stream,
  * and calls on different GPUs, are safe.
  */
@@ -336,6 +336,24 @@ int sage_attn_fwd_4bit(const void *q, const void *k, const void *v, void *out,
  * Returns SAGE_EINVAL for a bad argument, SAGE_EHIP if the launch failed.
  */
 int sage_diag_mfma_rate(int kind, int iters, int workgroups, float *sink, double *ops_per_launch, void *stream);
+
+/*
+ * Not a step of the method: selects, process-wide, which kernels the K/V quantisers (sage_quant_kv,
+ * sage_quant_kv_static, sage_quant_kv4 and the whole-pass entry points) launch.  Both choices compute the same
+ * codes, scales and mean (Sec. 2.1, Sec. 3).
+ *   path        0 (default): by shape — the single-read kernel (K and V are read once: the workgroups of a head
+ *               keep 64 KiB of tokens each in registers, exchange their partial column statistics through the
+ *               workspace and then write the codes) when a head is at most 128 such workgroups (32768 tokens at
+ *               d = 128, 65536 at d = 64), the three launches (statistics, finalize, codes; K and V read twice)
+ *               above that; 1: always the three launches; 2: always the single-read kernel (calls then fail with
+ *               SAGE_EHIP above 256 workgroups per head)
+ *   wait_ticks  how long a workgroup of the single-read kernel waits for the partials of its partners before it
+ *               computes the head's statistic alone from global memory (same result), in ticks of the GPU's
+ *               constant 100 MHz clock; negative: it does not wait at all (for tests of that branch); the
+ *               default is 200 000 (2 ms; partners normally arrive within microseconds)
+ * Returns SAGE_EINVAL for a path outside 0..2.  For benchmarks and tests; a production caller leaves it alone.
+ */
+int sage_diag_quant_kv_path(int path, long long wait_ticks);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ __all__ = [
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
     "sage_attn_fwd_strided", "sage_quant_kv", "sage_quant_kv_static", "workspace_bytes_gqa",
-    "v_fp8_to_token_major", "diag_mfma_rate", "EXPORTS", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s",
+    "v_fp8_to_token_major", "diag_mfma_rate", "diag_quant_kv_path", "EXPORTS", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s",
     "sage_attn_fwd_q4", "sage_attn_fwd_4bit", "workspace_bytes_4bit", "delta_s_to_key_order",
 ]
 
@@ -29,7 +29,7 @@ EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_w
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
            "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
-           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate", "sage_delta_s_bytes",
+           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate", "sage_diag_quant_kv_path", "sage_delta_s_bytes",
            "sage_workspace_bytes_4bit", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s", "sage_attn_fwd_q4",
            "sage_attn_fwd_4bit"]
 
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.sage_quant_kv_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp]
         L.sage_diag_mfma_rate.restype = i
         L.sage_diag_mfma_rate.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.sage_diag_quant_kv_path.restype = i
+        L.sage_diag_quant_kv_path.argtypes = [i, ctypes.c_longlong]
         L.sage_delta_s_bytes.restype = sz
         L.sage_delta_s_bytes.argtypes = [i, i, i, i]
         L.sage_workspace_bytes_4bit.restype = sz
@@ -223,6 +225,12 @@ def sage_quant_kv(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace:
                                v_fp8.data_ptr(), v_scale.data_ptr(), float(v_r), B, H, N, d, _dt(k), _stream(),
                                ws.data_ptr(), ws.numel()))
     return k_i8, k_scale, k_mean, v_fp8, v_scale
+
+
+def diag_quant_kv_path(path: int = 0, wait_ticks: int = 200_000) -> None:
+    """Select the kernels of the K/V quantisers (0: by shape, 1: three launches, 2: single-read kernel) and the
+    single-read kernel's wait bound; see include/sage.h.  For benchmarks and tests."""
+    _check(lib().sage_diag_quant_kv_path(int(path), int(wait_ticks)))
 
 
 def diag_mfma_rate(kind: int, iters: int = 4096, workgroups: int = 2048, repeats: int = 5) -> float:

@@ -273,8 +273,9 @@ int sage_quant_kv_static(const void *k, const void *v, int8_t *k_i8, float *k_sc
     void *ptr = nullptr;
     const hipError_t e = static_scratch(&ptr);
     if (e != hipSuccess) return from_hip(e);
-    // every partial statistic and every reciprocal the code pass reads is written by the statistics pass of the
-    // same call, so nothing in the scratch has to start at zero
+    // nothing in the scratch has to be cleared by the caller: the three launches write every partial statistic
+    // and reciprocal before they read it, and the single-read kernel's launcher clears the partial buffers with a
+    // fill kernel of its own in front
     const sage::QuantScratch ws = sage::quant_scratch_layout(ptr, B, H, N, d);
     const sage::Strides st = sage::contiguous_bhnd(H, N, d);
     return from_hip(sage::launch_quant_kv(k, st, v, st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, B, H, N, d,

@@ -81,3 +81,9 @@ extern "C" int sage_diag_mfma_rate(int kind, int iters, int workgroups, float *s
     }
     return hipGetLastError() == hipSuccess ? SAGE_OK : SAGE_EHIP;
 }
+
+extern "C" int sage_diag_quant_kv_path(int path, long long wait_ticks) {
+    if (path < 0 || path > 2) return SAGE_EINVAL;
+    sage::set_quant_kv_path(path, wait_ticks);
+    return SAGE_OK;
+}

@@ -47,6 +47,12 @@ hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v
                            float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int B, int H, int N, int d,
                            bool bf16, hipStream_t stream, const QuantScratch &ws, bool int4 = false);
 
+// Which kernels launch_quant_kv uses: 0 = by shape (the single-read kernel up to 128 workgroups per head),
+// 1 = always the three launches (statistics, finalize, codes), 2 = always the single-read kernel (error above 256
+// workgroups per head).  wait_ticks: how long a workgroup of the single-read kernel waits for its partners before
+// it computes the head's statistic alone (100 MHz ticks; negative: no wait).  Process-wide.
+void set_quant_kv_path(int path, long long wait_ticks);
+
 // 4+8 variant.  Block means of Q ([B,H,ceil(N/kBQ),d]); with q_i4 != NULL also the stand-alone INT4 codes and
 // scales of Q minus its block means.
 hipError_t launch_quant_q4(const void *q, Strides q_st, float *q_mean, int8_t *q_i4, float *q_scale, int B, int H, int N,

@@ -13,6 +13,9 @@
 // (paper Sec. 2.1 for the scales, Sec. 3 for the smoothing).
 #include "sage_internal.h"
 
+#include <algorithm>
+#include <atomic>
+
 namespace sage {
 namespace {
 
@@ -455,6 +458,425 @@ __global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restric
         quant_v_body<BF16, D>(V, v_st, H, v_rcp, Vt, N, nT, tile, blockIdx.y, x - nK);
 }
 
+// ---------------------------------------------------------------------------
+// K and V quantised with ONE read of each tensor (smoothing of Sec. 3, scales of Sec. 2.1; the same binary32
+// steps and the same outputs as the three launches above).  The codes of a token need a statistic of its whole
+// head (the K mean, the V maxima), so a token must wait somewhere between the statistics and the codes: here it
+// waits in registers.  A workgroup of 256 threads loads kResidentBytes of one (head, tensor) — 256 tokens at
+// d = 128, 512 at d = 64 — keeps them as 16 packed uint4 per thread, publishes its partial column statistic,
+// and then waits for the partials of all G = ceil(N / tokens) workgroups of the (head, tensor).  A partial is
+// its own "there" flag: the partial buffers are zero at launch (the host enqueues zero_words_kernel in front)
+// and a value is stored with a bit pattern that is never all zero (+0.0 goes out as -0.0, which adds and
+// compares like it), each with one write-through store that is atomic for its 4 or 8 bytes.  Thread t first
+// polls element 0 of partial t, sleeping between polls, for at most `wait_ticks` ticks of the constant 100 MHz
+// clock; once those are there every workgroup loads all G x d values (again until none is zero) and adds them
+// itself, in index order, so all workgroups of a head see the same statistic (workgroup 0 of the group also
+// writes it out: mean, or delta_V).  No workgroup waits for another one to do work on its behalf: the only chain
+// is "partial stored -> partial seen".  A workgroup whose wait runs out (its partners not resident: another
+// kernel holds the CUs, or a dispatch order other than by index) computes the head's statistic itself from
+// global memory and goes on, so every wavefront leaves the kernel whatever the others do.
+// Workgroup ids are group-major, and the hardware dispatches them in id order, so the G partners are resident
+// together as long as G does not exceed the workgroups the chip holds; since every workgroup reads G partials the
+// host takes this path only up to kResidentMaxGroup.  Grid: B*H*2*G; group 2*bh is K of head bh, 2*bh + 1 is V.
+// ---------------------------------------------------------------------------
+constexpr int kResidentBytes = 65536;
+constexpr int kResidentMaxGroup = 128;       // largest group the shape-based choice takes (every workgroup reads G partials:
+                                             // measured faster than the three launches up to here, 17-26 % slower at 192-256)
+constexpr int kResidentHardMaxGroup = 256;   // largest group a forced choice may take (one flag per thread)
+constexpr long long kResidentWaitTicks = 200000;  // 2 ms
+inline int resident_group_size(int N, int d) { return cdiv(N, kResidentBytes / (2 * d)); }
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint4 *w, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) w[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+
+// The packed rows stay packed between the passes over them: without this the compiler keeps the unpacked
+// floats of one pass alive for the next (twice the registers of the packed rows).
+__device__ __forceinline__ void keep_packed(uint4 (&raw)[16]) {
+#pragma unroll
+    for (int it = 0; it < 16; ++it) asm volatile("" : "+v"(raw[it].x), "+v"(raw[it].y), "+v"(raw[it].z), "+v"(raw[it].w));
+}
+
+// What the workgroups of a group tell each other goes through device-scope relaxed atomic accesses: stores
+// that write through to memory and loads that do not take a line another XCD's L2 may hold stale.  No cache is
+// written back or invalidated as a whole (a device-scope release fence does that, per wavefront, and with a
+// few thousand workgroups writing codes at the same time it costs ten times the kernel's own work).
+template <class T>
+__device__ __forceinline__ void put_shared(T *p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T>
+__device__ __forceinline__ T get_shared(const T *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The bit pattern a partial is stored with (never all zero) and read back from.
+__device__ __forceinline__ unsigned long long tag_bits(double a) {
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, a);
+    return b ? b : 0x8000000000000000ull;
+}
+__device__ __forceinline__ unsigned tag_bits(float a) {
+    const unsigned b = __builtin_bit_cast(unsigned, a);
+    return b ? b : 0x80000000u;
+}
+
+// Wait until element 0 of each of the G partials (rows of d words) is there.  True when they are, false when
+// the wait ran out (workgroup-uniform).  Contains a barrier in every case.
+template <class W>
+__device__ __forceinline__ bool resident_wait(const W *rows, int d, int G, long long wait_ticks, long long t0) {
+    if (wait_ticks < 0) {
+        __syncthreads();
+        return false;
+    }
+    for (;;) {
+        int v = 0;
+        if ((int)threadIdx.x < G && get_shared(&rows[(size_t)threadIdx.x * d]) == 0) v = 1;  // partner t is not there
+        if (wall_clock64() - t0 >= wait_ticks) v |= 2;                                      // my time is up
+        const int any = __syncthreads_or(v);
+        if (!(any & 1)) return true;
+        if (any & 2) return false;
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
+template <bool BF16, int D, int QMAX>
+__global__ __launch_bounds__(256, 4) void quant_kv_resident_kernel(
+    const uint16_t *__restrict__ K, Strides k_st, const uint16_t *__restrict__ V, Strides v_st, int H, int N, int G,
+    double *k_sum_part, float *v_max_part, float *k_mean, float *v_scale, float v_r,
+    int8_t *__restrict__ k_codes, float *__restrict__ k_scale, int nK, uint8_t *__restrict__ Vt, int nT,
+    long long wait_ticks) {
+    constexpr int C = kResidentBytes / (2 * D);  // tokens of a workgroup
+    constexpr int LPR = D / 8;                   // lanes per row
+    constexpr int RP = 256 / LPR;                // rows per pass of the workgroup
+    constexpr int NU = 16;                       // uint4 per thread
+    static_assert(C * LPR == NU * 256, "a workgroup's chunk is 16 uint4 per thread");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[16384];
+    __shared__ float stat[D];      // the head's mean (K) or V_r / max (V)
+    __shared__ float wmax[4][8];   // per wavefront and K block: max |K'|
+
+    const int grp = blockIdx.x / G, part = blockIdx.x % G;
+    const int bh = grp >> 1;
+    const bool is_v = grp & 1;  // (workgroup-uniform)
+    const int tid = threadIdx.x;
+    const int co = tid % LPR, rr = tid / LPR;
+    const int row0 = part * C;
+    unsigned long long *k_bits = reinterpret_cast<unsigned long long *>(k_sum_part);
+    unsigned *v_bits = reinterpret_cast<unsigned *>(v_max_part);
+    uint4 raw[NU];
+
+    if (!is_v) {
+        // ---- K: thread owns channels co*8.. of rows row0 + it*RP + rr ----
+        const uint16_t *Kh = K + (bh / H) * k_st.b + (bh % H) * k_st.h;
+        // (all sixteen loads are issued before the first is waited for: rows past the end are loaded from the
+        // head's last row and zeroed afterwards — a branch around a load would make each load wait for itself)
+        const int nrow = min(max((N - row0 - rr + RP - 1) / RP, 0), NU);  // this thread's rows that exist
+        {
+            const uint16_t *last = Kh + (int64_t)(N - 1) * k_st.n + co * 8;
+            const uint16_t *p = Kh + (int64_t)(row0 + rr) * k_st.n + co * 8;
+            const int64_t step = (int64_t)RP * k_st.n;
+#pragma unroll
+            for (int it = 0; it < NU; ++it) raw[it] = *reinterpret_cast<const uint4 *>(it < nrow ? p + it * step : last);
+        }
+#pragma unroll
+        for (int it = 0; it < NU; ++it)
+            if (it >= nrow) raw[it] = make_uint4(0u, 0u, 0u, 0u);
+        double(*smd)[D] = reinterpret_cast<double(*)[D]>(smem);
+        {
+            double acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+#pragma unroll
+            for (int it = 0; it < NU; ++it) {
+                float f[8];
+                unpack8<BF16>(raw[it], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += (double)f[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) smd[rr][co * 8 + j] = acc[j];
+        }
+        __syncthreads();
+        if (tid < D) {
+            double a = smd[0][tid];
+            for (int i = 1; i < RP; ++i) a += smd[i][tid];
+            put_shared(&k_bits[((size_t)bh * G + part) * D + tid], tag_bits(a));
+        }
+        const long long t0 = wall_clock64();
+        bool there = resident_wait(k_bits + (size_t)bh * G * D, D, G, wait_ticks, t0);
+        if (there) {
+            // the G partial sums in index order, 256 / D threads per channel (eight loads in flight: each is a
+            // round trip to memory); repeated in the rare case that a word of a partial lags behind its element 0
+            const int c = tid % D, share = tid / D;
+            constexpr int SHARES = 256 / D;
+            double s;
+            for (;;) {
+                s = 0.0;
+                int v = 0;
+                for (int i0 = share; i0 < G; i0 += 8 * SHARES) {
+                    unsigned long long t[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        t[u] = get_shared(&k_bits[((size_t)bh * G + min(i0 + u * SHARES, G - 1)) * D + c]);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (t[u] == 0) v = 1;
+                        if (i0 + u * SHARES < G) s += __builtin_bit_cast(double, t[u]);
+                    }
+                }
+                if (wall_clock64() - t0 >= wait_ticks) v |= 2;
+                const int any = __syncthreads_or(v);
+                if (!(any & 1)) break;
+                if (any & 2) {
+                    there = false;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (there) {
+                double *sd = reinterpret_cast<double *>(smem);
+                sd[tid] = s;
+                __syncthreads();
+                if (share == 0) {
+                    for (int k = 1; k < SHARES; ++k) s += sd[k * D + c];
+                    const float mu = (float)(s / (double)N);
+                    if (part == 0) k_mean[(size_t)bh * D + c] = mu;
+                    stat[c] = mu;
+                }
+            }
+        }
+        if (!there) {
+            // alone: the column sums of the whole head, from global memory
+            double acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+#pragma unroll 1
+            for (int r = rr; r < N; r += RP) {
+                float f[8];
+                unpack8<BF16>(*reinterpret_cast<const uint4 *>(Kh + r * k_st.n + co * 8), f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += (double)f[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) smd[rr][co * 8 + j] = acc[j];
+            __syncthreads();
+            if (tid < D) {
+                double a = smd[0][tid];
+                for (int i = 1; i < RP; ++i) a += smd[i][tid];
+                const float mu = (float)(a / (double)N);
+                if (part == 0) k_mean[(size_t)bh * D + tid] = mu;
+                stat[tid] = mu;
+            }
+        }
+        __syncthreads();
+
+        // ---- codes: the quantiser of quant_int8_body on the resident rows, C / kBK blocks at once ----
+        constexpr int NB = C / kBK;    // K blocks of the chunk
+        constexpr int IPB = kBK / RP;  // passes per block
+        constexpr float kRange = (float)QMAX;
+        float mu[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mu[j] = stat[co * 8 + j];
+        keep_packed(raw);
+        float amax[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float a = 0.0f;
+#pragma unroll
+            for (int i = 0; i < IPB; ++i) {
+                const int it = b * IPB + i;
+                if (it < nrow) {
+                    float f[8];
+                    unpack8<BF16>(raw[it], f);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(f[j] - mu[j]));
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) a = fmaxf(a, __shfl_xor(a, off));
+            amax[b] = a;
+        }
+        if ((tid & 63) == 0) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) wmax[tid >> 6][b] = amax[b];
+        }
+        keep_packed(raw);
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float a = fmaxf(fmaxf(wmax[0][b], wmax[1][b]), fmaxf(wmax[2][b], wmax[3][b]));
+            const float rcp = a > 0.0f ? kRange / a : 0.0f;
+            const int blk = part * NB + b;
+            if (tid == 0 && blk < nK) k_scale[(size_t)bh * nK + blk] = a / kRange;
+#pragma unroll
+            for (int i = 0; i < IPB; ++i) {
+                const int it = b * IPB + i;
+                const int r = row0 + it * RP + rr;
+                if (it < nrow) {
+                    float f[8];
+                    unpack8<BF16>(raw[it], f);
+                    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int c = (int)__builtin_rintf((f[j] - mu[j]) * rcp);
+                        w[j >> 2] |= ((uint32_t)c & 0xffu) << (8 * (j & 3));
+                    }
+                    *reinterpret_cast<uint2 *>(k_codes + ((size_t)bh * N + r) * D + co * 8) = make_uint2(w[0], w[1]);
+                }
+            }
+        }
+    } else {
+        // ---- V: per 128-key tile a thread owns UPT units of 4 consecutive keys x 8 channels (quant_v_body) ----
+        constexpr int UPT = 32 * LPR / 256;
+        constexpr int TILES = C / kW;
+        static_assert(TILES * UPT * 4 == NU, "a workgroup's chunk is 16 uint4 per thread");
+        const uint16_t *Vh = V + (bh / H) * v_st.b + (bh % H) * v_st.h;
+        // this thread's rows are row0 + (tid / LPR) * 4 + (kW / UPT) * (q >> 2) + (q & 3), q = 0 .. 15
+        uint32_t exists = 0u;
+        {
+            const uint16_t *last = Vh + (int64_t)(N - 1) * v_st.n + co * 8;
+            const int rbase = row0 + rr * 4;
+            const uint16_t *p = Vh + (int64_t)rbase * v_st.n + co * 8;
+#pragma unroll
+            for (int q = 0; q < NU; ++q) {
+                const int dr = (kW / UPT) * (q >> 2) + (q & 3);
+                const bool ok = rbase + dr < N;
+                exists |= (ok ? 1u : 0u) << q;
+                raw[q] = *reinterpret_cast<const uint4 *>(ok ? p + dr * v_st.n : last);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NU; ++q)
+            if (!((exists >> q) & 1u)) raw[q] = make_uint4(0u, 0u, 0u, 0u);
+        float(*smf)[D] = reinterpret_cast<float(*)[D]>(smem);
+        {
+            float acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll
+            for (int it = 0; it < NU; ++it) {
+                float f[8];
+                unpack8<BF16>(raw[it], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = fmaxf(acc[j], fabsf(f[j]));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) smf[rr][co * 8 + j] = acc[j];
+        }
+        __syncthreads();
+        if (tid < D) {
+            float a = smf[0][tid];
+            for (int i = 1; i < RP; ++i) a = fmaxf(a, smf[i][tid]);
+            put_shared(&v_bits[((size_t)bh * G + part) * D + tid], tag_bits(a));
+        }
+        const long long t0 = wall_clock64();
+        bool there = resident_wait(v_bits + (size_t)bh * G * D, D, G, wait_ticks, t0);
+        if (there) {
+            const int c = tid % D, share = tid / D;
+            constexpr int SHARES = 256 / D;
+            float a;
+            for (;;) {
+                a = 0.0f;
+                int v = 0;
+                for (int i0 = share; i0 < G; i0 += 16 * SHARES) {
+                    unsigned t[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        t[u] = get_shared(&v_bits[((size_t)bh * G + min(i0 + u * SHARES, G - 1)) * D + c]);
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        if (t[u] == 0u) v = 1;
+                        a = fmaxf(a, fabsf(__builtin_bit_cast(float, t[u])));  // (a partial taken twice does not change a maximum)
+                    }
+                }
+                if (wall_clock64() - t0 >= wait_ticks) v |= 2;
+                const int any = __syncthreads_or(v);
+                if (!(any & 1)) break;
+                if (any & 2) {
+                    there = false;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (there) {
+                float *sf = reinterpret_cast<float *>(smem);
+                sf[tid] = a;
+                __syncthreads();
+                if (share == 0) {
+                    for (int k = 1; k < SHARES; ++k) a = fmaxf(a, sf[k * D + c]);
+                    if (part == 0) v_scale[(size_t)bh * D + c] = a / v_r;
+                    stat[c] = a > 0.0f ? v_r / a : 0.0f;
+                }
+            }
+        }
+        if (!there) {
+            float acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll 1
+            for (int r = rr; r < N; r += RP) {
+                float f[8];
+                unpack8<BF16>(*reinterpret_cast<const uint4 *>(Vh + r * v_st.n + co * 8), f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = fmaxf(acc[j], fabsf(f[j]));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) smf[rr][co * 8 + j] = acc[j];
+            __syncthreads();
+            if (tid < D) {
+                float a = smf[0][tid];
+                for (int i = 1; i < RP; ++i) a = fmaxf(a, smf[i][tid]);
+                if (part == 0) v_scale[(size_t)bh * D + tid] = a / v_r;
+                stat[tid] = a > 0.0f ? v_r / a : 0.0f;
+            }
+        }
+        __syncthreads();
+
+        float rc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) rc[j] = stat[co * 8 + j];
+        keep_packed(raw);
+        uint32_t *tile = reinterpret_cast<uint32_t *>(smem);  // D * 32 dwords
+#pragma unroll
+        for (int tl = 0; tl < TILES; ++tl) {
+            const int T = part * TILES + tl;  // (workgroup-uniform)
+            if (T >= nT) break;
+#pragma unroll
+            for (int k = 0; k < UPT; ++k) {
+                const int kq = (tid + 256 * k) / LPR;
+                const int t = kq >> 2, g = kq & 3;
+                // two channels (one packed dword of each of the four keys) at a time; rows >= N hold zeros
+#pragma unroll
+                for (int j2 = 0; j2 < 4; ++j2) {
+                    float y[4][2];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint4 &u = raw[(tl * UPT + k) * 4 + i];
+                        const uint32_t w16 = j2 == 0 ? u.x : j2 == 1 ? u.y : j2 == 2 ? u.z : u.w;
+                        y[i][0] = to_f32<BF16>(w16 & 0xffffu) * rc[2 * j2];
+                        y[i][1] = to_f32<BF16>(w16 >> 16) * rc[2 * j2 + 1];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int j = 2 * j2 + e;
+                        int w = 0;
+                        w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0][e], y[1][e], w, false);
+                        w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2][e], y[3][e], w, true);
+                        tile[(co * 8 + j) * 32 + (t >> 2) * 16 + g * 4 + (t & 3)] = (uint32_t)w;
+                    }
+                }
+            }
+            __syncthreads();
+            uint4 *dst = reinterpret_cast<uint4 *>(Vt + ((size_t)bh * nT + T) * D * 128);
+            const uint4 *src = reinterpret_cast<const uint4 *>(tile);
+#pragma unroll
+            for (int k = 0; k < D / 32; ++k) dst[tid + 256 * k] = src[tid + 256 * k];
+            __syncthreads();
+        }
+    }
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <bool BF16, int D>
@@ -504,6 +926,24 @@ hipError_t quant_kv_impl(const uint16_t *k, Strides k_st, const uint16_t *v, Str
     return hipGetLastError();
 }
 
+// The same outputs from one read of K and V (quant_kv_resident_kernel); the caller has checked that the
+// group size fits.
+template <bool BF16, int D, int QMAX>
+hipError_t quant_kv_resident_impl(const uint16_t *k, Strides k_st, const uint16_t *v, Strides v_st, int8_t *k_i8,
+                                  float *k_scale, float *k_mean, uint8_t *v_fp8, float *v_scale, float v_r, int BH,
+                                  int H, int N, hipStream_t stream, const QuantScratch &ws, long long wait_ticks) {
+    const int G = resident_group_size(N, D);
+    const int nK = cdiv(N, kBK), nT = cdiv(N, kW);
+    // both partial buffers, which lie back to back (each a multiple of 256 bytes)
+    const size_t span = reinterpret_cast<char *>(ws.v_rcp) - reinterpret_cast<char *>(ws.k_sum_part);
+    const int words = (int)(span / 16);
+    zero_words_kernel<<<cdiv(words, 256), 256, 0, stream>>>(reinterpret_cast<uint4 *>(ws.k_sum_part), words);
+    quant_kv_resident_kernel<BF16, D, QMAX><<<BH * 2 * G, 256, 0, stream>>>(
+        k, k_st, v, v_st, H, N, G, ws.k_sum_part, ws.v_max_part, k_mean, v_scale, v_r, k_i8, k_scale,
+        nK, v_fp8, nT, wait_ticks);
+    return hipGetLastError();
+}
+
 // 4+8 variant, Q side: block means, and (stand-alone) the INT4 codes of Q minus its block means
 template <bool BF16, int D>
 hipError_t q4_impl(const uint16_t *q, Strides st, float *q_mean, int8_t *q_i4, float *q_scale, int BH, int H, int N,
@@ -517,9 +957,20 @@ hipError_t q4_impl(const uint16_t *q, Strides st, float *q_mean, int8_t *q_i4, f
 
 }  // namespace
 
+// which path launch_quant_kv takes (0: by shape) and how long a workgroup of the single-read kernel waits for its
+// partners (ticks of the 100 MHz clock; negative: not at all)
+std::atomic<int> g_kv_path{0};
+std::atomic<long long> g_kv_wait_ticks{kResidentWaitTicks};
+
+void set_quant_kv_path(int path, long long wait_ticks) {
+    g_kv_path.store(path);
+    g_kv_wait_ticks.store(wait_ticks);
+}
+
 QuantScratch quant_scratch_layout(void *base, int B, int H, int N, int d) {
     const size_t BH = (size_t)B * H;
-    const size_t chunks = (size_t)cdiv(N, kStatRows);
+    // partial statistics: one per kStatRows tokens (three-launch path) or per resident chunk (single-read path)
+    const size_t chunks = (size_t)std::max(cdiv(N, kStatRows), resident_group_size(N, d));
     char *p = static_cast<char *>(base);
     QuantScratch ws;
     size_t off = 0;
@@ -572,8 +1023,15 @@ hipError_t launch_quant_kv(const void *k, Strides k_st, const void *v, Strides v
                            bool bf16, hipStream_t stream, const QuantScratch &ws, bool int4) {
     const uint16_t *k16 = static_cast<const uint16_t *>(k), *v16 = static_cast<const uint16_t *>(v);
     const int BH = B * H;
-#define SAGE_KV(BF, DD, QM) \
-    quant_kv_impl<BF, DD, QM>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, BH, H, N, stream, ws)
+    const int path = g_kv_path.load();
+    const bool resident = path == 2 || (path == 0 && resident_group_size(N, d) <= kResidentMaxGroup);
+    if (resident && resident_group_size(N, d) > kResidentHardMaxGroup) return hipErrorInvalidValue;
+    const long long wait_ticks = g_kv_wait_ticks.load();
+#define SAGE_KV(BF, DD, QM)                                                                                           \
+    (resident ? quant_kv_resident_impl<BF, DD, QM>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, \
+                                                   BH, H, N, stream, ws, wait_ticks)                                 \
+              : quant_kv_impl<BF, DD, QM>(k16, k_st, v16, v_st, k_i8, k_scale, k_mean, v_fp8, v_scale, v_r, BH, H, N, \
+                                          stream, ws))
     if (int4) {
         if (d == 128) return bf16 ? SAGE_KV(true, 128, 7) : SAGE_KV(false, 128, 7);
         return bf16 ? SAGE_KV(true, 64, 7) : SAGE_KV(false, 64, 7);
