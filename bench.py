@@ -76,6 +76,10 @@ def main():
     ap.add_argument("--staged-q", action="store_true",
                     help="quantise Q with the stand-alone kernel (sage_quant_q + sage_attn_fwd_quantized) instead "
                          "of inside the attention kernel; same result bit for bit, for comparison")
+    ap.add_argument("--quant-path", choices=["auto", "three-launches", "single-read"], default="auto",
+                    help="kernels of the K/V quantisation stage: chosen by shape (default), always the three "
+                         "launches (statistics, finalize, codes: K and V read twice), or always the single-read "
+                         "kernel; same result bit for bit, for comparison")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the live measurement of the matrix-pipe rate (roofline.peak_measured)")
     ap.add_argument("--mfma-table", action="store_true",
@@ -101,6 +105,7 @@ def main():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         sys.exit(2)
     sage.lib()
+    sage.diag_quant_kv_path({"auto": 0, "three-launches": 1, "single-read": 2}[args.quant_path])
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.mfma_table:
@@ -225,7 +230,8 @@ def main():
                         f"[{prof['source']}]") if prof else None,
         },
         "quant_stage": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_gbs, 1) if quant_gbs else None,
-                        "frac_of_hbm_peak": round(quant_gbs * 1e9 / PEAK_HBM, 4) if quant_gbs else None},
+                        "frac_of_hbm_peak": round(quant_gbs * 1e9 / PEAK_HBM, 4) if quant_gbs else None,
+                        "kernels": args.quant_path},
     }
 
     if not args.no_cpu_baseline:

@@ -671,7 +671,8 @@ __global__ __launch_bounds__(256, 4) void quant_kv_resident_kernel(
         }
         __syncthreads();
 
-        // ---- codes: the quantiser of quant_int8_body on the resident rows, C / kBK blocks at once ----
+        // ---- codes: the quantiser of quant_int8_body on the resident rows, one K block after the other; the
+        // smoothed values of a block stay in registers between its maximum and its codes ----
         constexpr int NB = C / kBK;    // K blocks of the chunk
         constexpr int IPB = kBK / RP;  // passes per block
         constexpr float kRange = (float)QMAX;
@@ -679,48 +680,46 @@ __global__ __launch_bounds__(256, 4) void quant_kv_resident_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) mu[j] = stat[co * 8 + j];
         keep_packed(raw);
-        float amax[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
+            const int blk = part * NB + b;  // (workgroup-uniform)
+            if (blk >= nK) break;
+            float x[IPB][8];
             float a = 0.0f;
 #pragma unroll
             for (int i = 0; i < IPB; ++i) {
-                const int it = b * IPB + i;
-                if (it < nrow) {
-                    float f[8];
-                    unpack8<BF16>(raw[it], f);
+                float f[8];
+                unpack8<BF16>(raw[b * IPB + i], f);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(f[j] - mu[j]));
+                for (int j = 0; j < 8; ++j) x[i][j] = f[j] - mu[j];
+                if (b * IPB + i < nrow) {  // rows past the end do not count
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(x[i][j]));
                 }
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) a = fmaxf(a, __shfl_xor(a, off));
-            amax[b] = a;
-        }
-        if ((tid & 63) == 0) {
-#pragma unroll
-            for (int b = 0; b < NB; ++b) wmax[tid >> 6][b] = amax[b];
-        }
-        keep_packed(raw);
-        __syncthreads();
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const float a = fmaxf(fmaxf(wmax[0][b], wmax[1][b]), fmaxf(wmax[2][b], wmax[3][b]));
+            if ((tid & 63) == 0) wmax[tid >> 6][b] = a;
+            __syncthreads();  // (every block has its own column of wmax: one barrier per block)
+            a = fmaxf(fmaxf(wmax[0][b], wmax[1][b]), fmaxf(wmax[2][b], wmax[3][b]));
             const float rcp = a > 0.0f ? kRange / a : 0.0f;
-            const int blk = part * NB + b;
-            if (tid == 0 && blk < nK) k_scale[(size_t)bh * nK + blk] = a / kRange;
+            if (tid == 0) k_scale[(size_t)bh * nK + blk] = a / kRange;
 #pragma unroll
             for (int i = 0; i < IPB; ++i) {
                 const int it = b * IPB + i;
                 const int r = row0 + it * RP + rr;
                 if (it < nrow) {
-                    float f[8];
-                    unpack8<BF16>(raw[it], f);
-                    uint32_t w[2] = {0u, 0u};
+                    // rint(y) for |y| <= 127 as the low byte of fl(y + 1.5 * 2^23): the addition rounds y to the
+                    // nearest integer, ties to even, and the sum's bit pattern is 0x4B400000 + that integer
+                    uint32_t cb[8];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const int c = (int)__builtin_rintf((f[j] - mu[j]) * rcp);
-                        w[j >> 2] |= ((uint32_t)c & 0xffu) << (8 * (j & 3));
+                    for (int j = 0; j < 8; ++j) cb[j] = __builtin_bit_cast(uint32_t, x[i][j] * rcp + 12582912.0f);
+                    uint32_t w[2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t lo = __builtin_amdgcn_perm(cb[4 * h + 1], cb[4 * h], 0x0c0c0400u);
+                        const uint32_t hi = __builtin_amdgcn_perm(cb[4 * h + 3], cb[4 * h + 2], 0x0c0c0400u);
+                        w[h] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                     }
                     *reinterpret_cast<uint2 *>(k_codes + ((size_t)bh * N + r) * D + co * 8) = make_uint2(w[0], w[1]);
                 }
