@@ -71,6 +71,9 @@ def _load():
         lib.sage_oracle_quant_int.argtypes = [vp, vp, c_i, c_i, c_i, c_i, c_i, vp, vp]
         lib.sage_oracle_delta_s.restype = None
         lib.sage_oracle_delta_s.argtypes = [vp, vp, c_i, c_i, c_i, vp]
+        lib.sage_oracle_attn_rows_split.restype = None
+        lib.sage_oracle_attn_rows_split.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
+                                                    c_i, c_i, c_i, c_i, c_i, c_i, c_i, vp]
         lib.sage_oracle_attn_rows_blockmax.restype = None
         lib.sage_oracle_attn_rows_blockmax.argtypes = [vp, vp, vp, vp, vp, vp, c_i, c_i, c_i, c_i, c_d, c_d,
                                                        c_i, c_i, c_i, c_i, c_i, c_i, vp]
@@ -245,8 +248,11 @@ def sage_attention_head_4bit(q, k, v, *, causal: bool, sm_scale: float, out_dtyp
 # --------------------------------------------------------------------------
 def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: float = P_R,
               bq: int = BQ, bk: int = BK, w: int = W, row0: int = 0, row1=None,
-              out_dtype="bf16", want_p: bool = False, delta_p: str = "static", dS=None):
+              out_dtype="bf16", want_p: bool = False, delta_p: str = "static", dS=None, split_keys=None):
     """Quantised attention of query rows [row0, row1): Q^ is [Nq, d], K^ and V^ are [Nk, d].
+
+    split_keys (a multiple of w, or None): evaluate key ranges of that many keys independently and combine
+    them (the library's decode path; see sage_oracle_attn_rows_split).
 
     delta_p = "static" (the method as built: delta_P = 1/P_r) or "block_max" (Section 3.1 Eq. 2 read literally:
     delta_P = max(P~)/P_r per (Q block x key step); a study mode, CPU only).
@@ -267,6 +273,12 @@ def attn_rows(Qc, Kc, Vc, dq, dk, dv, *, causal: bool, sm_scale: float, p_r: flo
     if dS is not None:
         dS = _c(dS, np.float64)
         assert dS.shape == ((Nq + bq - 1) // bq, Nk) and delta_p == "static"
+    if split_keys is not None:
+        assert delta_p == "static" and dS is None and not want_p and split_keys >= w and split_keys % w == 0
+        _load().sage_oracle_attn_rows_split(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),
+                                            float(sm_scale), float(p_r), bq, bk, w, int(split_keys), row0, row1, code,
+                                            _p(out))
+        return out
     if delta_p == "block_max":
         assert not want_p
         _load().sage_oracle_attn_rows_blockmax(_p(Qc), _p(Kc), _p(Vc), _p(dq), _p(dk), _p(dv), Nq, Nk, d, int(causal),

@@ -411,6 +411,99 @@ void sage_oracle_attn_rows(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc
     free(Vd);
 }
 
+/* Key-split evaluation of the same attention (not in the paper; the decode-shaped path of the library).
+ * The keys are cut into ranges of `split_keys` keys (a multiple of W).  For every row and every range the
+ * recurrence of sage_oracle_attn_rows is run on the keys of that range alone, from m = -inf, l = 0,
+ * acc = 0 -- so P~ is taken against the running maximum of the RANGE before its FP8 rounding, which is what
+ * makes this a mode of its own and not a reordering -- and gives (m_s, l_s, acc_s).  The ranges are then
+ * combined the way two partial softmax sums always combine:
+ *     m = max_s m_s,   l = sum_s 2^(m_s - m) l_s,   acc = sum_s 2^(m_s - m) acc_s,
+ *     O[r][c] = acc[c] * delta_V[c] / (P_r * l),
+ * a range in which the row sees no key (causal mask) contributing nothing.  With split_keys >= Nk this is
+ * sage_oracle_attn_rows.  Arguments as there (no P_out, no dS).                                           */
+void sage_oracle_attn_rows_split(const int8_t *Qc, const int8_t *Kc, const uint8_t *Vc,
+                                 const float *dq, const float *dk, const float *dv,
+                                 int Nq, int Nk, int d, int causal, double sm_scale, double p_r,
+                                 int BQ, int BK, int W, int split_keys, int row0, int row1, int out_dtype,
+                                 double *out)
+{
+    const int N = Nk;
+    const int shift = Nk - Nq;
+    (void)Nq;
+    double *Vd = (double *)malloc((size_t)N * d * sizeof(double));
+    for (size_t i = 0; i < (size_t)N * d; ++i)
+        Vd[i] = sage_oracle_e4m3_decode(Vc[i]);
+
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)W * sizeof(double));
+        double *acc = (double *)malloc((size_t)d * sizeof(double));   /* of the current range */
+        double *tot = (double *)malloc((size_t)d * sizeof(double));   /* combined so far */
+#pragma omp for schedule(dynamic, 1)
+        for (int r = row0; r < row1; ++r) {
+            const int8_t *qr = Qc + (size_t)r * d;
+            int last = causal ? r + shift : N - 1;
+            double M = -INFINITY, L = 0.0;
+            for (int c = 0; c < d; ++c)
+                tot[c] = 0.0;
+            for (int k0 = 0; k0 <= last; k0 += split_keys) {
+                int k1 = k0 + split_keys < N ? k0 + split_keys : N;
+                double m = -INFINITY, l = 0.0;
+                for (int c = 0; c < d; ++c)
+                    acc[c] = 0.0;
+                for (int t0 = k0; t0 < k1 && t0 <= last; t0 += W) {
+                    int t1 = t0 + W < k1 ? t0 + W : k1;
+                    double mx = -INFINITY;
+                    for (int n = t0; n < t1; ++n) {
+                        if (n > last) {
+                            x[n - t0] = -INFINITY;
+                            continue;
+                        }
+                        const int8_t *kn = Kc + (size_t)n * d;
+                        int32_t s = 0;
+                        for (int c = 0; c < d; ++c)
+                            s += (int32_t)qr[c] * (int32_t)kn[c];
+                        x[n - t0] = (double)s * ((double)dq[r / BQ] * (double)dk[n / BK] * sm_scale * SAGE_ORACLE_LOG2E);
+                        if (x[n - t0] > mx)
+                            mx = x[n - t0];
+                    }
+                    double m_new = m > mx ? m : mx;   /* finite: key t0 <= last is visible */
+                    double alpha = exp2(m - m_new);
+                    l *= alpha;
+                    for (int c = 0; c < d; ++c)
+                        acc[c] *= alpha;
+                    for (int n = t0; n < t1; ++n) {
+                        double p = isinf(x[n - t0]) ? 0.0 : exp2(x[n - t0] - m_new);
+                        l += p;
+                        double ph = sage_oracle_e4m3_decode(sage_oracle_e4m3_encode(p * p_r));
+                        if (ph != 0.0) {
+                            const double *vn = Vd + (size_t)n * d;
+                            for (int c = 0; c < d; ++c)
+                                acc[c] += ph * vn[c];
+                        }
+                    }
+                    m = m_new;
+                }
+                /* combine the range with what came before */
+                double Mn = M > m ? M : m;
+                double a = exp2(M - Mn), b = exp2(m - Mn);   /* M = -inf for the first range gives a = 0 */
+                L = a * L + b * l;
+                for (int c = 0; c < d; ++c)
+                    tot[c] = a * tot[c] + b * acc[c];
+                M = Mn;
+            }
+            for (int c = 0; c < d; ++c) {
+                double o = tot[c] * (double)dv[c] / (p_r * L);
+                out[(size_t)(r - row0) * d + c] = out_dtype < 0 ? o : sage_oracle_round16(o, out_dtype);
+            }
+        }
+        free(x);
+        free(acc);
+        free(tot);
+    }
+    free(Vd);
+}
+
 /* Study variant of sage_oracle_attn_rows: Section 3.1, Eq. (2) read literally.  There the scale of P~ is
  * taken per block, delta_P = max(P~) / P_r, a block of P~ being one Q block (BQ rows) times one key step
  * (W keys); the routine above uses the constant delta_P = 1 / P_r instead (P~ <= 1 by construction, and a
