@@ -20,7 +20,8 @@ __all__ = [
     "sage_quant_qk", "sage_quant_q", "sage_quant_k", "sage_quant_v", "sage_attn_fwd_quantized",
     "sage_attn_fwd_quantized_gqa", "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa",
     "sage_attn_fwd_strided", "sage_quant_kv", "sage_quant_kv_static", "workspace_bytes_gqa",
-    "v_fp8_to_token_major", "diag_mfma_rate", "diag_quant_kv_path", "EXPORTS", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s",
+    "v_fp8_to_token_major", "diag_mfma_rate", "diag_quant_kv_path", "decode_split_keys", "decode_workspace_bytes",
+    "sage_attn_fwd_decode", "EXPORTS", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s",
     "sage_attn_fwd_q4", "sage_attn_fwd_4bit", "workspace_bytes_4bit", "delta_s_to_key_order",
 ]
 
@@ -29,7 +30,8 @@ EXPORTS = ["sage_get_params", "sage_strerror", "sage_v_fp8_bytes", "sage_quant_w
            "sage_workspace_bytes", "sage_workspace_bytes_gqa", "sage_quant_qk", "sage_quant_q", "sage_quant_k",
            "sage_quant_v", "sage_attn_fwd_quantized", "sage_attn_fwd_quantized_gqa",
            "sage_attn_fwd_kvquantized_gqa", "sage_attn_fwd", "sage_attn_fwd_gqa", "sage_attn_fwd_strided",
-           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate", "sage_diag_quant_kv_path", "sage_delta_s_bytes",
+           "sage_quant_kv", "sage_quant_kv_static", "sage_diag_mfma_rate", "sage_diag_quant_kv_path", "sage_decode_split_keys", "sage_decode_workspace_bytes",
+           "sage_attn_fwd_decode", "sage_delta_s_bytes",
            "sage_workspace_bytes_4bit", "sage_quant_q4", "sage_quant_kv4", "sage_delta_s", "sage_attn_fwd_q4",
            "sage_attn_fwd_4bit"]
 
@@ -84,6 +86,12 @@ def lib() -> ctypes.CDLL:
         L.sage_quant_kv_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, i, i, i, i, i, vp]
         L.sage_diag_mfma_rate.restype = i
         L.sage_diag_mfma_rate.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.sage_decode_split_keys.restype = i
+        L.sage_decode_split_keys.argtypes = [i, i, i]
+        L.sage_decode_workspace_bytes.restype = sz
+        L.sage_decode_workspace_bytes.argtypes = [i, i, i, i, i]
+        L.sage_attn_fwd_decode.restype = i
+        L.sage_attn_fwd_decode.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, i, vp, vp, sz]
         L.sage_diag_quant_kv_path.restype = i
         L.sage_diag_quant_kv_path.argtypes = [i, ctypes.c_longlong]
         L.sage_delta_s_bytes.restype = sz
@@ -335,6 +343,37 @@ def sage_attn_fwd_kvquantized_gqa(q, k_i8, v_fp8, k_scale, v_scale, *, causal: b
     _check(lib().sage_attn_fwd_kvquantized_gqa(q.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
                                                v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d, int(causal),
                                                float(sm_scale), float(p_r), _dt(q), _stream()))
+    return out
+
+
+def decode_split_keys(B: int, Hkv: int, Nk: int) -> int:
+    """Keys per range that sage_attn_fwd_decode uses for split_keys = 0."""
+    return int(lib().sage_decode_split_keys(B, Hkv, Nk))
+
+
+def decode_workspace_bytes(B: int, Hkv: int, Nk: int, d: int, split_keys: int = 0) -> int:
+    return int(lib().sage_decode_workspace_bytes(B, Hkv, Nk, d, split_keys))
+
+
+def sage_attn_fwd_decode(q, k_i8, v_fp8, k_scale, v_scale, *, causal: bool, sm_scale: float = 0.0,
+                         p_r: float = 224.0, split_keys: int = 0, out: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None):
+    """Decode-shaped attention: q [B,Hq,Nq,d] with (Hq/Hkv)*Nq <= 16 against quantised k_i8 [B,Hkv,Nk,d] / v_fp8;
+    the keys are evaluated in ranges of split_keys keys (0: the library's choice) and combined."""
+    _dev(q, k_i8, v_fp8, k_scale, v_scale)
+    B, Hq, Nq, d = q.shape
+    _, Hkv, Nk, _ = k_i8.shape
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out)
+    if out.dtype != q.dtype:
+        raise SageError("out must have q's dtype")
+    need = decode_workspace_bytes(B, Hkv, Nk, d, split_keys)
+    ws = workspace if workspace is not None else _workspace(max(need, 256), q.device)
+    _check(lib().sage_attn_fwd_decode(q.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
+                                      v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d, int(causal),
+                                      float(sm_scale), float(p_r), int(split_keys), _dt(q), _stream(), ws.data_ptr(),
+                                      ws.numel()))
     return out
 
 

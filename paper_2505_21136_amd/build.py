@@ -19,6 +19,7 @@ RESOURCES = os.path.join(OBJDIR, "kernel_resources.txt")
 UNITS = [
     ("sage_quant.hip", ["-ffp-contract=off"]),
     ("sage_attn.hip", []),
+    ("sage_decode.hip", []),
     ("sage_api.hip", []),
     ("sage_diag.hip", []),
 ]
@@ -27,6 +28,7 @@ UNITS = [
 def sources():
     out = [os.path.join(CSRC, u) for u, _ in UNITS]
     out.append(os.path.join(CSRC, "sage_internal.h"))
+    out.append(os.path.join(CSRC, "sage_attn_device.h"))
     out.append(os.path.join(os.path.dirname(HERE), "include", "sage.h"))
     return out
 

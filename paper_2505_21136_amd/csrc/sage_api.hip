@@ -410,6 +410,46 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
                                       static_cast<hipStream_t>(stream)));
 }
 
+/* ---- decode-shaped calls -------------------------------------------------------------------------------- */
+
+namespace {
+bool decode_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, int split_keys) {
+    return gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) && (Hq / Hkv) * Nq <= 16 && split_keys >= 0 &&
+           split_keys % sage::kW == 0;
+}
+int decode_steps(int B, int Hkv, int Nk, int split_keys) {
+    return split_keys > 0 ? split_keys / sage::kW : sage::decode_auto_steps_per_split(B, Hkv, Nk);
+}
+}  // namespace
+
+int sage_decode_split_keys(int B, int Hkv, int Nk) {
+    if (B < 1 || Hkv < 1 || Nk < 1 || Nk > (1 << 22)) return 0;
+    return sage::decode_auto_steps_per_split(B, Hkv, Nk) * sage::kW;
+}
+
+size_t sage_decode_workspace_bytes(int B, int Hkv, int Nk, int d, int split_keys) {
+    if (!shape_ok(B, Hkv, Nk, d) || split_keys < 0 || split_keys % sage::kW != 0) return 0;
+    return sage::decode_scratch_layout(nullptr, B, Hkv, Nk, d, decode_steps(B, Hkv, Nk, split_keys)).bytes;
+}
+
+int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                         const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal,
+                         float sm_scale, float p_r, int split_keys, sage_dtype dt, void *stream, void *workspace,
+                         size_t workspace_bytes) {
+    if (!decode_ok(B, Hq, Hkv, Nq, Nk, d, causal, split_keys) || !dtype_ok(dt)) return SAGE_EINVAL;
+    if (!q || !k_i8 || !v_fp8 || !k_scale || !v_scale || !out) return SAGE_EINVAL;
+    if (!aligned16(q) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
+        return SAGE_EINVAL;
+    if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
+    const int steps = decode_steps(B, Hkv, Nk, split_keys);
+    const sage::DecodeScratch ws = sage::decode_scratch_layout(workspace, B, Hkv, Nk, d, steps);
+    if (!workspace || !aligned256(workspace) || workspace_bytes < ws.bytes) return SAGE_EWORKSPACE;
+    sm_scale = scale_or_default(sm_scale, d);
+    discard_pending_hip_error();
+    return from_hip(sage::launch_decode(q, k_i8, v_fp8, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal != 0,
+                                        sm_scale, p_r, steps, dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+}
+
 int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,
                             const float *k_scale, const float *v_scale, void *out, int B, int H, int N, int d,
                             int causal, float sm_scale, float p_r, sage_dtype out_dt, void *stream) {
