@@ -95,6 +95,76 @@ def test_ranges_against_the_oracle_on_the_same_ranges(idx, B, Hq, Hkv, Nq, Nk, d
                   f"decode B{B} Hq{Hq}/{Hkv} Nq{Nq} Nk{Nk} d{d} split {used}", flip_factor=2.0)
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(9000 + seed)
+    group = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    Nq = int(rng.integers(1, 16 // group + 1))
+    Hkv = int(rng.choice([1, 2, 3]))
+    B = int(rng.integers(1, 5))
+    d = int(rng.choice([64, 128]))
+    Nk = int(rng.choice([rng.integers(Nq, 130), rng.integers(130, 700), rng.integers(700, 3000)]))
+    causal = bool(rng.integers(0, 2))
+    split = int(rng.choice([0, 128, 256, 512]))
+    idx = int(rng.choice([1, 3, 5]))
+    return idx, B, Hkv * group, Hkv, Nq, Nk, d, causal, split
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_decode_shapes(seed):
+    idx, B, Hq, Hkv, Nq, Nk, d, causal, split_keys = _random_case(seed)
+    used = split_keys or sage.decode_split_keys(B, Hkv, Nk)
+    say(f"[decode] seed {seed}: cfg{idx} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} causal={causal} ranges of {used}")
+    q, k, v, sm = _inputs(idx, B, Hq, Hkv, Nq, Nk, d)
+    out, _ = _gpu(q, k, v, causal, sm, split_keys)
+    want = _oracle(q, k, v, causal, sm, used)
+    got = out.cpu().to(torch.float64).numpy()
+    assert np.isfinite(got).all()
+    # few rows: the norms of the gate and the worst row, not the flip statistics of large blocks
+    m_cos = float((want * got).sum() / np.sqrt((want * want).sum() * (got * got).sum()))
+    rel = float(np.abs(want - got).sum() / np.abs(want).sum())
+    assert m_cos >= 0.9999 and rel <= 1e-3, (m_cos, rel)
+    assert_parity(want.reshape(-1, d), got.reshape(-1, d), "bf16" if q.dtype == torch.bfloat16 else "fp16",
+                  f"decode seed {seed}", flip_factor=4.0)
+
+
+def test_decode_call_can_be_replayed_from_a_hip_graph():
+    """Two launches, no memset, no allocation: captured once, replayed with other data in the same buffers."""
+    B, Hq, Hkv, Nq, Nk, d = 2, 8, 2, 2, 1500, 128
+    q, k, v, sm = _inputs(2, B, Hq, Hkv, Nq, Nk, d)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
+    ws = torch.empty(sage.decode_workspace_bytes(B, Hkv, Nk, d, 256), dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(qd)
+    eager = sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256,
+                                      workspace=ws).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):      # warm-up on the capture stream
+        sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256,
+                                  out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256,
+                                  out=out, workspace=ws)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), rep
+    q2 = torch.flip(qd, dims=[1]).contiguous()
+    want2 = sage.sage_attn_fwd_decode(q2, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256).clone()
+    qd.copy_(q2)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want2.view(torch.int16))
+
+
 def test_long_cache_with_the_library_split():
     """The shape the path is for: B 8, 32 / 8 heads, one query row over 32768 keys; all heads of two K/V heads
     against the oracle."""
