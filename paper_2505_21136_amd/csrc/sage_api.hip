@@ -414,7 +414,7 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
 
 namespace {
 bool decode_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, int split_keys) {
-    return gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) && (Hq / Hkv) * Nq <= 16 && split_keys >= 0 &&
+    return gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) && (Hq / Hkv) * Nq <= 64 && split_keys >= 0 &&
            split_keys % sage::kW == 0;
 }
 int decode_steps(int B, int Hkv, int Nk, int split_keys) {
@@ -427,9 +427,11 @@ int sage_decode_split_keys(int B, int Hkv, int Nk) {
     return sage::decode_auto_steps_per_split(B, Hkv, Nk) * sage::kW;
 }
 
-size_t sage_decode_workspace_bytes(int B, int Hkv, int Nk, int d, int split_keys) {
+size_t sage_decode_workspace_bytes(int B, int Hkv, int Nk, int d, int split_keys, int rows_per_kv_head) {
     if (!shape_ok(B, Hkv, Nk, d) || split_keys < 0 || split_keys % sage::kW != 0) return 0;
-    return sage::decode_scratch_layout(nullptr, B, Hkv, Nk, d, decode_steps(B, Hkv, Nk, split_keys)).bytes;
+    if (rows_per_kv_head < 1 || rows_per_kv_head > 64) return 0;
+    return sage::decode_scratch_layout(nullptr, B, Hkv, Nk, d, decode_steps(B, Hkv, Nk, split_keys),
+                                       sage::cdiv(rows_per_kv_head, 16)).bytes;
 }
 
 int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
@@ -442,7 +444,8 @@ int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
     const int steps = decode_steps(B, Hkv, Nk, split_keys);
-    const sage::DecodeScratch ws = sage::decode_scratch_layout(workspace, B, Hkv, Nk, d, steps);
+    const sage::DecodeScratch ws =
+        sage::decode_scratch_layout(workspace, B, Hkv, Nk, d, steps, sage::cdiv((Hq / Hkv) * Nq, 16));
     if (!workspace || !aligned256(workspace) || workspace_bytes < ws.bytes) return SAGE_EWORKSPACE;
     sm_scale = scale_or_default(sm_scale, d);
     discard_pending_hip_error();

@@ -4,11 +4,12 @@
 // The prefill kernel gives a workgroup 128 query rows of one head and shares every K^/V^ tile among its eight
 // wavefronts through LDS.  Here a head has at most a handful of rows, so that shape leaves 7 of 8 wavefronts
 // and 15 of 16 MFMA columns idle and B*Hq workgroups cannot fill 256 CUs.  Instead:
-//   * the R = (Hq/Hkv) * Nq <= 16 query rows of all query heads that share one K/V head are packed into the 16
-//     columns of ONE MFMA tile (exact: every row keeps its own scale, running maximum and sum), so K^ and V^ of
-//     a head are streamed once for all of them;
+//   * the R = (Hq/Hkv) * Nq <= 64 query rows of all query heads that share one K/V head are packed into the 16
+//     columns of T = ceil(R/16) <= 4 MFMA tiles (exact: every row keeps its own scale, running maximum and sum), so
+//     K^ and V^ of a head leave HBM once for all of them (the T wavefronts of a range sit in one workgroup and
+//     read the same tiles at the same time: all but the first hit L2);
 //   * the keys are cut into ranges of `steps_per_split` key steps and ONE WAVEFRONT owns one (batch, K/V head,
-//     range): it runs the step recurrence on its range from m = -inf, l = 0, acc = 0 and writes (m, l, acc) per
+//     range, row tile): it runs the step recurrence on its range from m = -inf, l = 0, acc = 0 and writes (m, l, acc) per
 //     row; merge_kernel then combines the ranges as partial softmax sums (m = max m_s, weights 2^(m_s - m));
 //   * a wavefront uses each tile exactly once, so the operands go global -> registers directly (16 bytes per
 //     lane and load, in the lane order the MFMA wants), K^ of step j+1 and V^ of step j in flight under the
@@ -23,13 +24,13 @@ namespace sage {
 namespace {
 
 // D: head dimension; CAUSAL: end-aligned mask (key n visible to row r iff n <= r + Nk - Nq); BF16: type of Q / O.
-// Grid: ceil(B*Hkv*S / 4) workgroups of 4 wavefronts; wavefront w = (b*Hkv + kvh)*S + split.
+// Grid: ceil(B*Hkv*S*T / 4) workgroups of 4 wavefronts; wavefront w = ((b*Hkv + kvh)*S + split)*T + row tile.
 template <int D, bool CAUSAL, bool BF16>
 __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restrict__ Q, const int8_t *__restrict__ Kc,
                                                         const uint8_t *__restrict__ Vt, const float *__restrict__ dk,
                                                         float *__restrict__ part_acc, float *__restrict__ part_ml,
                                                         int n_waves, int Hq, int Hkv, int group, int Nq, int Nk, int nT,
-                                                        int nKblk, int S, int steps_per_split, float sm_scale,
+                                                        int nKblk, int S, int T, int steps_per_split, float sm_scale,
                                                         float log2_pr) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int KC = D / 64;  // 64-wide contraction chunks of Q.K^T
@@ -38,13 +39,15 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
     const int w = __builtin_amdgcn_readfirstlane((int)blockIdx.x * 4 + (int)(threadIdx.x >> 6));
     if (w >= n_waves) return;  // (whole wavefronts leave; the kernel has no barrier)
     const int lq = lane & 15, g = lane >> 4;
-    const int split = w % S, bhk = w / S;
+    const int rt = w % T, split = (w / T) % S, bhk = w / (T * S);
     const int b = bhk / Hkv, kvh = bhk % Hkv;
-    const int R = group * Nq;  // rows in use (<= 16)
-    // row lq of the tile = query row r of query head hq (rows past R repeat row 0 of head 0 and are never stored)
-    const bool row_ok = lq < R;
-    const int hq = kvh * group + (row_ok ? lq / Nq : 0);
-    const int r = row_ok ? lq % Nq : 0;
+    const int R = group * Nq;  // rows in use (<= 16 * T)
+    // row 16*rt + lq of the K/V head = query row r of query head hq (rows past R repeat row 0 of head 0 and are
+    // never stored)
+    const int ri = 16 * rt + lq;
+    const bool row_ok = ri < R;
+    const int hq = kvh * group + (row_ok ? ri / Nq : 0);
+    const int r = row_ok ? ri % Nq : 0;
     const int shift = Nk - Nq;
 
     const int8_t *Kh = Kc + (size_t)bhk * Nk * D;
@@ -69,14 +72,23 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
                 for (int i = 0; i < 4; ++i)
                     amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(u[i] & 0xffffu)), fabsf(to_f32<BF16>(u[i] >> 16))));
             }
-        amax = rowgroup_max(amax);  // over the four lanes of a row: the row's maximum
-        // over the rows of the same head (rows [hd*Nq, hd*Nq + Nq) of the tile)
-        const int hd = lq / Nq;
-        float a = 0.0f;
-        for (int j = 0; j < 16; ++j) {
-            const float other = __shfl(amax, j);  // row j's maximum (lane j holds it like every lane of that row)
-            if (j / Nq == hd && j < R) a = fmaxf(a, other);
+        // the head's maximum: this lane's channels of all Nq rows of its head (they may sit in another row tile),
+        // then over the four lanes that share the row
+        const uint16_t *Qhd = Q + ((size_t)b * Hq + hq) * Nq * D;
+        for (int rr = 0; rr < Nq; ++rr) {
+            if (rr == r) continue;
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint4 x = *reinterpret_cast<const uint4 *>(Qhd + (size_t)rr * D + ch * 64 + g * 16 + h * 8);
+                    const uint32_t u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        amax = fmaxf(amax, fmaxf(fabsf(to_f32<BF16>(u[i] & 0xffffu)), fabsf(to_f32<BF16>(u[i] >> 16))));
+                }
         }
+        float a = rowgroup_max(amax);
         if (!row_ok) a = 0.0f;
         const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
         delta_q = a / 127.0f;
@@ -205,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
 template <int D, bool BF16>
 __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ part_acc, const float *__restrict__ part_ml,
                                                     const float *__restrict__ dv, uint16_t *__restrict__ out, int Hq,
-                                                    int Hkv, int group, int Nq, int S) {
+                                                    int Hkv, int group, int Nq, int S, int T) {
     constexpr int Q4 = D / 4;      // channel quads
     constexpr int SL = 256 / Q4;   // range lanes
     __shared__ float red[256];
@@ -213,12 +225,14 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
     __shared__ float l_s[SL];
     const int row = blockIdx.x;  // (b*Hq + hq)*Nq + r
     const int r = row % Nq, bh = row / Nq, hq = bh % Hq, b = bh / Hq;
-    const int kvh = hq / group, i = (hq % group) * Nq + r;
-    const size_t w0 = ((size_t)b * Hkv + kvh) * S;
+    const int kvh = hq / group, ri = (hq % group) * Nq + r;  // row ri of the K/V head: tile ri / 16, column ri % 16
+    const int i = ri % 16;
+    // the partial results of range s sit at wavefront index w0 + s * T
+    const size_t w0 = ((size_t)b * Hkv + kvh) * S * T + ri / 16;
     const int tid = threadIdx.x, cq = tid % Q4, sl = tid / Q4;
     // the row's maximum over all ranges
     float mx = -INFINITY;
-    for (int s = tid; s < S; s += 256) mx = fmaxf(mx, part_ml[((w0 + s) * 16 + i) * 2]);
+    for (int s = tid; s < S; s += 256) mx = fmaxf(mx, part_ml[((w0 + (size_t)s * T) * 16 + i) * 2]);
     red[tid] = mx;
     __syncthreads();
     for (int k = 128; k >= 1; k >>= 1) {
@@ -230,8 +244,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
     for (int s = sl; s < S; s += SL) {
-        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + ((w0 + s) * 16 + i) * 2);
-        const float4 a = *reinterpret_cast<const float4 *>(part_acc + ((w0 + s) * 16 + i) * D + 4 * cq);
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + ((w0 + (size_t)s * T) * 16 + i) * 2);
+        const float4 a = *reinterpret_cast<const float4 *>(part_acc + ((w0 + (size_t)s * T) * 16 + i) * D + 4 * cq);
         // a range in which the row saw no key has m = -inf, l = 0, acc = 0: its weight 2^(-inf) = 0 is exact
         const float wgt = __builtin_amdgcn_exp2f(ml.x - mx);
         l = __builtin_fmaf(wgt, ml.y, l);
@@ -267,9 +281,9 @@ int decode_auto_steps_per_split(int B, int Hkv, int Nk) {
     return std::max(std::min(nT, 2), cdiv(nT, want));
 }
 
-DecodeScratch decode_scratch_layout(void *base, int B, int Hkv, int Nk, int d, int steps_per_split) {
+DecodeScratch decode_scratch_layout(void *base, int B, int Hkv, int Nk, int d, int steps_per_split, int row_tiles) {
     const int S = cdiv(cdiv(Nk, kW), steps_per_split);
-    const size_t waves = (size_t)B * Hkv * S;
+    const size_t waves = (size_t)B * Hkv * S * row_tiles;
     char *p = static_cast<char *>(base);
     DecodeScratch ws;
     ws.n_splits = S;
@@ -288,13 +302,14 @@ hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
     const int group = Hq / Hkv;
     const int nT = cdiv(Nk, kW), nK = cdiv(Nk, kBK);
     const int S = ws.n_splits;
-    const int n_waves = B * Hkv * S;
+    const int T = cdiv(group * Nq, 16);
+    const int n_waves = B * Hkv * S * T;
     const float log2_pr = (float)log2((double)p_r);
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     uint16_t *o16 = static_cast<uint16_t *>(out);
 #define SAGE_DEC(DD, C, BF)                                                                                          \
     decode_kernel<DD, C, BF><<<cdiv(n_waves, 4), 256, 0, stream>>>(q16, k_i8, v_fp8, k_scale, ws.part_acc, ws.part_ml, \
-                                                                   n_waves, Hq, Hkv, group, Nq, Nk, nT, nK, S,       \
+                                                                   n_waves, Hq, Hkv, group, Nq, Nk, nT, nK, S, T,    \
                                                                    steps_per_split, sm_scale, log2_pr)
     if (d == 128) {
         if (causal) { if (bf16) SAGE_DEC(128, true, true); else SAGE_DEC(128, true, false); }
@@ -306,7 +321,7 @@ hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
 #undef SAGE_DEC
     const int n_rows = B * Hq * Nq;
 #define SAGE_MERGE(DD, BF) \
-    merge_kernel<DD, BF><<<n_rows, 256, 0, stream>>>(ws.part_acc, ws.part_ml, v_scale, o16, Hq, Hkv, group, Nq, S)
+    merge_kernel<DD, BF><<<n_rows, 256, 0, stream>>>(ws.part_acc, ws.part_ml, v_scale, o16, Hq, Hkv, group, Nq, S, T)
     if (d == 128) {
         if (bf16) SAGE_MERGE(128, true); else SAGE_MERGE(128, false);
     } else {

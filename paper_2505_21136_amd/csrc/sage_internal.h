@@ -74,17 +74,18 @@ hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_
                        int Nq, int Nk, int d, bool causal, float sm_scale, float p_r, bool bf16_out,
                        hipStream_t stream, const float *q_mean = nullptr, const float *dsx = nullptr);
 
-// Decode-shaped attention (sage_decode.hip): (Hq/Hkv)*Nq <= 16 query rows per K/V head, the keys cut into ranges of
-// `steps_per_split` key steps; one wavefront per (batch, K/V head, range) writes its (m, l, acc) per row into the
-// scratch, a second launch combines the ranges.  q and out are contiguous [B,Hq,Nq,d].
+// Decode-shaped attention (sage_decode.hip): (Hq/Hkv)*Nq <= 64 query rows per K/V head in T = ceil(rows/16) row
+// tiles, the keys cut into ranges of `steps_per_split` key steps; one wavefront per (batch, K/V head, range, row
+// tile) writes its (m, l, acc) per row into the scratch, a second launch combines the ranges.  q and out are
+// contiguous [B,Hq,Nq,d].
 struct DecodeScratch {
-    float *part_acc;  // [B*Hkv][S][16][d]  un-normalised outputs of every range
-    float *part_ml;   // [B*Hkv][S][16][2]  running maximum and sum of every range
+    float *part_acc;  // [B*Hkv][S][T][16][d]  un-normalised outputs of every range
+    float *part_ml;   // [B*Hkv][S][T][16][2]  running maximum and sum of every range
     int n_splits;     // S = ceil(ceil(Nk/128) / steps_per_split)
     size_t bytes;
 };
 int decode_auto_steps_per_split(int B, int Hkv, int Nk);
-DecodeScratch decode_scratch_layout(void *base, int B, int Hkv, int Nk, int d, int steps_per_split);
+DecodeScratch decode_scratch_layout(void *base, int B, int Hkv, int Nk, int d, int steps_per_split, int row_tiles);
 hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
                          const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d, bool causal,
                          float sm_scale, float p_r, int steps_per_split, bool bf16, hipStream_t stream,

@@ -9,7 +9,7 @@ Inputs are seeded normal draws (K with a per-channel bias, as in the benchmark w
 Prints one JSON line per shape: milliseconds per call (HIP events over `--steps` calls after a warm-up) and
 attention TOPS = 4 * B * Hq * (visible query-key pairs) * d / t.
 
-With --decode the shape must be decode-shaped ((Hq/Hkv)*Nq <= 16): K and V are quantised once outside the timed
+With --decode the shape must be decode-shaped ((Hq/Hkv)*Nq <= 64): K and V are quantised once outside the timed
 region (as a decode loop over a fixed cache would) and two attention-only calls are timed on them,
 sage_attn_fwd_decode (query heads packed, key ranges) and sage_attn_fwd_kvquantized_gqa (the prefill kernel on the
 same shape), with the rate at which each streams the quantised cache (2 * B * Hkv * Nk * d bytes per call).
@@ -84,7 +84,8 @@ def run_decode(shape: str, steps: int, warm_s: float) -> dict:
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(k, v, 4.5)
     del k, v
     out = torch.empty_like(q)
-    ws = torch.empty(max(256, sage.decode_workspace_bytes(B, Hkv, Nk, d, 0)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(256, sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, (Hq // Hkv) * Nq)), dtype=torch.uint8,
+                     device="cuda")
     sm = 1.0 / d ** 0.5
 
     def dec():

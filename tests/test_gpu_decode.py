@@ -59,6 +59,9 @@ ONE_RANGE = [  # idx, B, Hq, Hkv, Nq, Nk, d, causal
     (1, 2, 4, 4, 1, 700, 128, False), (2, 1, 8, 2, 2, 1000, 128, True), (3, 2, 6, 2, 5, 300, 64, True),
     (5, 1, 16, 1, 1, 129, 128, False), (4, 2, 2, 2, 16, 513, 64, True), (1, 1, 3, 3, 7, 64, 128, True),
     (5, 2, 8, 8, 1, 1, 128, True),
+    # more than 16 rows per K/V head: several row tiles, heads that straddle them
+    (2, 2, 8, 2, 5, 600, 128, True), (3, 1, 4, 1, 16, 1000, 64, True), (5, 1, 16, 2, 3, 257, 128, False),
+    (1, 2, 2, 2, 33, 400, 128, True),
 ]
 
 
@@ -78,6 +81,7 @@ RANGES = [  # idx, B, Hq, Hkv, Nq, Nk, d, causal, split_keys (0: the library's c
     (3, 4, 8, 8, 3, 1500, 64, True, 512), (4, 2, 32, 4, 1, 4096, 64, False, 0),
     (5, 4, 8, 1, 2, 777, 128, True, 128), (5, 8, 4, 4, 16, 300, 128, True, 128),
     (1, 8, 4, 2, 8, 129, 64, True, 128),
+    (2, 2, 8, 2, 5, 1500, 128, True, 256), (4, 2, 4, 1, 16, 2000, 64, True, 0), (5, 1, 24, 3, 7, 900, 128, False, 384),
 ]
 
 
@@ -98,7 +102,7 @@ def test_ranges_against_the_oracle_on_the_same_ranges(idx, B, Hq, Hkv, Nq, Nk, d
 def _random_case(seed):
     rng = np.random.default_rng(9000 + seed)
     group = int(rng.choice([1, 2, 3, 4, 8, 16]))
-    Nq = int(rng.integers(1, 16 // group + 1))
+    Nq = int(rng.integers(1, (16 if seed % 3 else 64) // group + 1))
     Hkv = int(rng.choice([1, 2, 3]))
     B = int(rng.integers(1, 5))
     d = int(rng.choice([64, 128]))
@@ -133,7 +137,7 @@ def test_decode_call_can_be_replayed_from_a_hip_graph():
     q, k, v, sm = _inputs(2, B, Hq, Hkv, Nq, Nk, d)
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
-    ws = torch.empty(sage.decode_workspace_bytes(B, Hkv, Nk, d, 256), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sage.decode_workspace_bytes(B, Hkv, Nk, d, 256, (Hq // Hkv) * Nq), dtype=torch.uint8, device=DEV)
     out = torch.empty_like(qd)
     eager = sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256,
                                       workspace=ws).clone()
@@ -185,7 +189,7 @@ def test_long_cache_with_the_library_split():
 
 
 def test_argument_errors():
-    q, k, v, sm = _inputs(1, 1, 8, 2, 5, 256, 128)        # (8/2)*5 = 20 rows per K/V head
+    q, k, v, sm = _inputs(1, 1, 16, 2, 9, 256, 128)       # (16/2)*9 = 72 rows per K/V head
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
     with pytest.raises(sage.SageError):
