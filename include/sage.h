@@ -379,7 +379,7 @@ int sage_diag_mfma_rate(int kind, int iters, int workgroups, float *sink, double
  *   wait_ticks  how long a workgroup of the single-read kernel waits for the partials of its partners before it
  *               computes the head's statistic alone from global memory (same result), in ticks of the GPU's
  *               constant 100 MHz clock; negative: it does not wait at all (for tests of that branch); the
- *               default is 200 000 (2 ms; partners normally arrive within microseconds)
+ *               default is 50 000 (0.5 ms; partners normally arrive within microseconds)
  * Returns SAGE_EINVAL for a path outside 0..2.  For benchmarks and tests; a production caller leaves it alone.
  */
 int sage_diag_quant_kv_path(int path, long long wait_ticks);

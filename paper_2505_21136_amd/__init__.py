@@ -235,7 +235,7 @@ def sage_quant_kv(k: torch.Tensor, v: torch.Tensor, v_r: float = 4.5, workspace:
     return k_i8, k_scale, k_mean, v_fp8, v_scale
 
 
-def diag_quant_kv_path(path: int = 0, wait_ticks: int = 200_000) -> None:
+def diag_quant_kv_path(path: int = 0, wait_ticks: int = 50_000) -> None:
     """Select the kernels of the K/V quantisers (0: by shape, 1: three launches, 2: single-read kernel) and the
     single-read kernel's wait bound; see include/sage.h.  For benchmarks and tests."""
     _check(lib().sage_diag_quant_kv_path(int(path), int(wait_ticks)))

@@ -483,7 +483,7 @@ constexpr int kResidentBytes = 65536;
 constexpr int kResidentMaxGroup = 128;       // largest group the shape-based choice takes (every workgroup reads G partials:
                                              // measured faster than the three launches up to here, 17-26 % slower at 192-256)
 constexpr int kResidentHardMaxGroup = 256;   // largest group a forced choice may take (one flag per thread)
-constexpr long long kResidentWaitTicks = 200000;  // 2 ms
+constexpr long long kResidentWaitTicks = 50000;  // 0.5 ms
 inline int resident_group_size(int N, int d) { return cdiv(N, kResidentBytes / (2 * d)); }
 
 __global__ __launch_bounds__(256) void zero_words_kernel(uint4 *w, int n) {
@@ -531,12 +531,11 @@ __device__ __forceinline__ bool resident_wait(const W *rows, int d, int G, long 
         return false;
     }
     for (;;) {
-        int v = 0;
-        if ((int)threadIdx.x < G && get_shared(&rows[(size_t)threadIdx.x * d]) == 0) v = 1;  // partner t is not there
-        if (wall_clock64() - t0 >= wait_ticks) v |= 2;                                      // my time is up
-        const int any = __syncthreads_or(v);
-        if (!(any & 1)) return true;
-        if (any & 2) return false;
+        const bool missing = (int)threadIdx.x < G && get_shared(&rows[(size_t)threadIdx.x * d]) == 0;  // partner t
+        const bool late = wall_clock64() - t0 >= wait_ticks;                                          // my time is up
+        // (__syncthreads_or tells WHETHER any thread's value is non-zero, not which bits: one call per question)
+        if (!__syncthreads_or(missing)) return true;
+        if (__syncthreads_or(late)) return false;
         __builtin_amdgcn_s_sleep(8);
     }
 }
@@ -625,10 +624,9 @@ __global__ __launch_bounds__(256, 4) void quant_kv_resident_kernel(
                         if (i0 + u * SHARES < G) s += __builtin_bit_cast(double, t[u]);
                     }
                 }
-                if (wall_clock64() - t0 >= wait_ticks) v |= 2;
-                const int any = __syncthreads_or(v);
-                if (!(any & 1)) break;
-                if (any & 2) {
+                const bool late = wall_clock64() - t0 >= wait_ticks;
+                if (!__syncthreads_or(v)) break;
+                if (__syncthreads_or(late)) {
                     there = false;
                     break;
                 }
@@ -789,10 +787,9 @@ __global__ __launch_bounds__(256, 4) void quant_kv_resident_kernel(
                         a = fmaxf(a, fabsf(__builtin_bit_cast(float, t[u])));  // (a partial taken twice does not change a maximum)
                     }
                 }
-                if (wall_clock64() - t0 >= wait_ticks) v |= 2;
-                const int any = __syncthreads_or(v);
-                if (!(any & 1)) break;
-                if (any & 2) {
+                const bool late = wall_clock64() - t0 >= wait_ticks;
+                if (!__syncthreads_or(v)) break;
+                if (__syncthreads_or(late)) {
                     there = false;
                     break;
                 }

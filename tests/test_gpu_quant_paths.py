@@ -24,7 +24,7 @@ def _restore_default_path():
     sage.diag_quant_kv_path(0)
 
 
-def _quant(k, v, v_r, path, wait_ticks=200_000):
+def _quant(k, v, v_r, path, wait_ticks=50_000):
     sage.diag_quant_kv_path(path, wait_ticks)
     out = sage.sage_quant_kv(k, v, v_r)
     torch.cuda.synchronize()
@@ -83,6 +83,18 @@ def test_workgroups_that_do_not_wait_compute_the_statistic_alone(idx, shape):
     _same_bits(three, alone, "no-wait single-read vs three launches")
 
 
+@pytest.mark.parametrize("wait_ticks", [0, 1, 100])
+@pytest.mark.parametrize("idx,shape", [(2, (2, 3, 2049, 128)), (4, (1, 2, 4500, 64))])
+def test_a_wait_that_runs_out_ends_in_the_stand_alone_branch(idx, shape, wait_ticks):
+    """The bounded wait itself: with a bound of 0, 10 ns or 1 us a workgroup polls once or a few times and, unless all
+    its partners are already there, gives up and computes the statistic alone.  Same bits, and the launch ends."""
+    say(f"[quant paths] wait bound {wait_ticks} ticks, cfg{idx} distributions, shape {shape}")
+    k, v = _inputs(idx, shape)
+    three = _quant(k, v, 4.5, THREE_LAUNCHES)
+    short = _quant(k, v, 4.5, SINGLE_READ, wait_ticks=wait_ticks)
+    _same_bits(three, short, f"wait bound {wait_ticks}")
+
+
 def test_repeated_calls_reuse_the_workspace():
     """The partial buffers, whose zero words mean "not there yet", are cleared by the call itself: back-to-back
     calls on one workspace that starts full of garbage, the second on other data, each give their own result."""
@@ -116,6 +128,33 @@ def test_partials_that_are_exactly_zero():
     single = _quant(k, v, 4.5, SINGLE_READ)
     _same_bits(three, single, "zero partials")
     _against_oracle(single, k, v, 4.5, 1024)
+
+
+def test_single_read_kernel_next_to_a_kernel_that_holds_the_cus():
+    """The workgroups of a head meet inside one launch.  With another stream's attention kernel holding the CUs the
+    partners of a workgroup may arrive late or (after the wait bound) not in time at all; the result must be the
+    same bits either way, and every launch must end."""
+    cfg = wl.CONFIGS[4].scaled(H=8)                       # B1 H8 N32768 d128: an attention launch of ~2.5 ms
+    q, kk, vv = (t.to(DEV) for t in wl.generate(cfg))
+    k, v = _inputs(2, (4, 16, 4096, 128))
+    want = _quant(k, v, 4.5, THREE_LAUNCHES)
+    sage.diag_quant_kv_path(SINGLE_READ, 20_000)          # 0.2 ms: short enough for some waits to run out
+    B, H, N, d = k.shape
+    ws = torch.empty(sage.quant_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=DEV)
+    ws_a = torch.empty(sage.workspace_bytes(cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.uint8, device=DEV)
+    out_a = torch.empty_like(q)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    got = []
+    for rep in range(3):
+        with torch.cuda.stream(side):
+            sage.sage_attn_fwd(q, kk, vv, causal=False, out=out_a, workspace=ws_a)
+            sage.sage_attn_fwd(q, kk, vv, causal=False, out=out_a, workspace=ws_a)
+        got.append(sage.sage_quant_kv(k, v, 4.5, workspace=ws))       # default stream, concurrent with `side`
+        got.append(sage.sage_quant_kv(k, v, 4.5, workspace=ws))
+        torch.cuda.synchronize()
+    for i, g in enumerate(got):
+        _same_bits(want, g, f"concurrent call {i}")
 
 
 @pytest.mark.parametrize("idx", [2, 3, 4, 5])
