@@ -474,7 +474,9 @@ __global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restric
 // writes it out: mean, or delta_V).  No workgroup waits for another one to do work on its behalf: the only chain
 // is "partial stored -> partial seen".  A workgroup whose wait runs out (its partners not resident: another
 // kernel holds the CUs, or a dispatch order other than by index) computes the head's statistic itself from
-// global memory and goes on, so every wavefront leaves the kernel whatever the others do.
+// global memory and goes on, so every wavefront leaves the kernel whatever the others do.  (The two questions of
+// a poll -- is a partial missing, has my time run out -- are two workgroup-wide reductions: __syncthreads_or only
+// tells whether any thread's value is non-zero.)
 // Workgroup ids are group-major, and the hardware dispatches them in id order, so the G partners are resident
 // together as long as G does not exceed the workgroups the chip holds; since every workgroup reads G partials the
 // host takes this path only up to kResidentMaxGroup.  Grid: B*H*2*G; group 2*bh is K of head bh, 2*bh + 1 is V.
@@ -482,7 +484,7 @@ __global__ __launch_bounds__(256) void quant_kv_kernel(const uint16_t *__restric
 constexpr int kResidentBytes = 65536;
 constexpr int kResidentMaxGroup = 128;       // largest group the shape-based choice takes (every workgroup reads G partials:
                                              // measured faster than the three launches up to here, 17-26 % slower at 192-256)
-constexpr int kResidentHardMaxGroup = 256;   // largest group a forced choice may take (one flag per thread)
+constexpr int kResidentHardMaxGroup = 256;   // largest group a forced choice may take (thread t polls partner t)
 constexpr long long kResidentWaitTicks = 50000;  // 0.5 ms
 inline int resident_group_size(int N, int d) { return cdiv(N, kResidentBytes / (2 * d)); }
 
