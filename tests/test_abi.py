@@ -95,6 +95,41 @@ def test_argument_checks_return_codes_without_touching_the_gpu():
         assert isinstance(L.sage_strerror(code), bytes) and len(L.sage_strerror(code)) > 0
 
 
+def test_decode_helpers_and_argument_checks_on_the_host():
+    """Range length, workspace size and the argument checks of the decode entry point are host arithmetic."""
+    L = sage.lib()
+    for B, Hkv, Nk in ((8, 8, 32768), (1, 8, 131072), (64, 8, 4096), (1, 1, 1), (2, 3, 129), (4096, 8, 1024)):
+        sk = sage.decode_split_keys(B, Hkv, Nk)
+        nT = -(-Nk // 128)
+        assert sk % 128 == 0 and 128 <= sk <= max(128, nT * 128)
+        ranges = -(-nT // (sk // 128))
+        assert ranges >= 1 and (nT < 2 or sk >= 256)           # at least two key steps per wavefront
+        assert B * Hkv * ranges <= max(B * Hkv, 2 * 2048 + B * Hkv)   # not many more wavefronts than asked for
+        for d in (64, 128):
+            one = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 16)
+            four = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 64)
+            assert one % 256 == 0 and one >= B * Hkv * ranges * 16 * (d + 2) * 4 and four >= 4 * one - 3 * 512
+            assert sage.decode_workspace_bytes(B, Hkv, Nk, d, sk, 16) == one
+    assert sage.decode_workspace_bytes(1, 1, 1024, 128, 100, 16) == 0      # not a multiple of 128
+    assert sage.decode_workspace_bytes(1, 1, 1024, 128, 128, 65) == 0      # more rows than the path takes
+    assert sage.decode_workspace_bytes(1, 1, 1024, 96, 128, 16) == 0
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255                    # never dereferenced: the checks fail first
+    EINVAL, EWS = -1, -2
+
+    def dec(Hq=8, Hkv=2, Nq=1, Nk=1024, d=128, causal=0, split=0, ws=p, wsb=16, q=p, p_r=224.0, dt=1):
+        return L.sage_attn_fwd_decode(q, p, p, p, p, p, 1, Hq, Hkv, Nq, Nk, d, causal, 0.0, p_r, split, dt, None, ws, wsb)
+
+    assert dec() == EWS                                         # a valid call reaches the workspace check
+    assert dec(Nq=16) == EWS and dec(Nq=17) == EINVAL           # (8/2)*16 = 64 rows per K/V head is the limit
+    assert dec(Hq=6, Hkv=4) == EINVAL                           # Hq not a multiple of Hkv
+    assert dec(split=100) == EINVAL and dec(split=-128) == EINVAL and dec(split=256) == EWS
+    assert dec(Nq=4, Nk=3, causal=1) == EINVAL                  # the end-aligned mask needs Nk >= Nq
+    assert dec(d=96) == EINVAL and dec(dt=5) == EINVAL and dec(p_r=0.0) == EINVAL
+    assert dec(q=None) == EINVAL and dec(q=p + 4) == EINVAL
+    assert dec(ws=None, wsb=1 << 30) == EWS
+
+
 def test_no_cpu_fallback():
     import torch
     q = torch.zeros((1, 1, 16, 64), dtype=torch.float16)
