@@ -337,7 +337,7 @@ int sage_attn_fwd_4bit(const void *q, const void *k, const void *v, void *out,
  *   k_i8 .. v_scale   device, as produced by sage_quant_k / sage_quant_v (or sage_quant_kv) for [B,Hkv,Nk,d]
  *   causal      mask aligned to the end of both sequences (key n visible to row r iff n <= r + Nk - Nq)
  *   split_keys  keys per range: a positive multiple of 128, or 0 for the library's choice, which
- *               sage_decode_split_keys(B, Hkv, Nk) reports (about eight wavefronts per CU over the launch)
+ *               sage_decode_split_keys(B, Hkv, Nk) reports (about four wavefronts per CU over the launch)
  *   workspace   device, 256-byte aligned, >= sage_decode_workspace_bytes(B, Hkv, Nk, d, split_keys,
  *               (Hq/Hkv) * Nq): the ranges' partial results; nothing in it has to be initialised
  * Returns SAGE_EINVAL for (Hq/Hkv) * Nq > 64 (use the prefill entry points), a split_keys that is negative or no

@@ -104,7 +104,7 @@ def test_decode_helpers_and_argument_checks_on_the_host():
         assert sk % 128 == 0 and 128 <= sk <= max(128, nT * 128)
         ranges = -(-nT // (sk // 128))
         assert ranges >= 1 and (nT < 2 or sk >= 256)           # at least two key steps per wavefront
-        assert B * Hkv * ranges <= max(B * Hkv, 2 * 2048 + B * Hkv)   # not many more wavefronts than asked for
+        assert B * Hkv * ranges <= max(B * Hkv, 2 * 1024 + B * Hkv)   # not many more wavefronts than asked for
         for d in (64, 128):
             one = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 16)
             four = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 64)
