@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
     const int j0 = split * steps_per_split, j1 = min(nT, j0 + steps_per_split);
 
     // ---- Q: load 16-bit, quantise per head over its Nq rows (the stand-alone quantiser's binary32 steps on one
-    // block of Nq <= 128 rows), straight into the B operand layout of the INT8 MFMA ----
+    // block of Nq <= 64 rows: a head's rows are one Q quantisation block), straight into the B operand layout of the INT8 MFMA ----
     v4i qreg[KC];
     float delta_q;
     {
