@@ -325,27 +325,32 @@ int sage_attn_fwd_4bit(const void *q, const void *k, const void *v, void *out,
 /* ---- decode-shaped calls ---------------------------------------------- */
 
 /*
- * Attention of a few query rows per head over a long, already quantised key sequence (the paper does not treat
- * this shape; a key step is evaluated exactly as in sage_attn_fwd_kvquantized_gqa, Sec. 2.1 / Sec. 3.1).
- * The (Hq/Hkv) * Nq <= 64 query rows of the query heads that share a K/V head are processed together, and the keys
- * are cut into ranges of `split_keys` keys that are evaluated independently -- each from an empty running maximum,
- * so P~ is rounded to FP8 against the maximum of its RANGE -- and then combined as partial softmax sums
- * (m = max m_s, l = sum 2^(m_s - m) l_s, O likewise).  With one range (split_keys >= Nk) the result is that of
- * sage_attn_fwd_kvquantized_gqa bit for bit; with more it differs from it by FP8 rounding decisions only.
- *   q, out      device, [B,Hq,Nq,d] contiguous, 16-bit type `dt`; Q is quantised inside (per head, its Nq rows are
- *               one quantisation block)
+ * Attention of few query rows over a long, already quantised key sequence: calls whose (head, query tile) pairs
+ * alone cannot fill the GPU (the paper does not treat this shape; a key step is evaluated exactly as in
+ * sage_attn_fwd_kvquantized_gqa, Sec. 2.1 / Sec. 3.1).  The keys are cut into ranges of `split_keys` keys that are
+ * evaluated independently -- each from an empty running maximum, so P~ is rounded to FP8 against the maximum of
+ * its RANGE -- and then combined as partial softmax sums (m = max m_s, l = sum 2^(m_s - m) l_s, O likewise).  With
+ * one range (split_keys >= Nk) the result is that of sage_attn_fwd_kvquantized_gqa bit for bit; with more it differs
+ * from it by FP8 rounding decisions only.
+ * Up to (Hq/Hkv) * Nq = 64 query rows per K/V head, the rows of all query heads that share a K/V head are packed
+ * into MFMA tiles of 16 and one wavefront takes one (K/V head, range, row tile), reading K^ and V^ straight from
+ * global memory; above that the prefill kernel runs with its key steps cut into ranges, one workgroup per
+ * (head, query tile, range).
+ *   q, out      device, [B,Hq,Nq,d] contiguous, 16-bit type `dt`; Q is quantised inside (per head and block of 128
+ *               rows, as everywhere)
  *   k_i8 .. v_scale   device, as produced by sage_quant_k / sage_quant_v (or sage_quant_kv) for [B,Hkv,Nk,d]
  *   causal      mask aligned to the end of both sequences (key n visible to row r iff n <= r + Nk - Nq)
  *   split_keys  keys per range: a positive multiple of 128, or 0 for the library's choice, which
- *               sage_decode_split_keys(B, Hkv, Nk) reports (about four wavefronts per CU over the launch)
- *   workspace   device, 256-byte aligned, >= sage_decode_workspace_bytes(B, Hkv, Nk, d, split_keys,
- *               (Hq/Hkv) * Nq): the ranges' partial results; nothing in it has to be initialised
- * Returns SAGE_EINVAL for (Hq/Hkv) * Nq > 64 (use the prefill entry points), a split_keys that is negative or no
- * multiple of 128, and the argument errors of the other entry points; SAGE_EWORKSPACE; SAGE_EHIP.
- * Two launches (ranges, combination); allocates nothing, does not synchronise.
+ *               sage_decode_split_keys(B, Hq, Hkv, Nq, Nk) reports (about four wavefronts, or workgroups, per CU
+ *               over the launch); a caller whose results must not depend on the batch size passes its own
+ *   workspace   device, 256-byte aligned, >= sage_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, split_keys): the
+ *               ranges' partial results; nothing in it has to be initialised
+ * Returns SAGE_EINVAL for a split_keys that is negative or no multiple of 128 and for the argument errors of the
+ * other entry points; SAGE_EWORKSPACE; SAGE_EHIP.  Two launches (ranges, combination); allocates nothing, does not
+ * synchronise.
  */
-int sage_decode_split_keys(int B, int Hkv, int Nk);
-size_t sage_decode_workspace_bytes(int B, int Hkv, int Nk, int d, int split_keys, int rows_per_kv_head);
+int sage_decode_split_keys(int B, int Hq, int Hkv, int Nq, int Nk);
+size_t sage_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d, int split_keys);
 int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8,
                          const float *k_scale, const float *v_scale, void *out,
                          int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, float sm_scale, float p_r,

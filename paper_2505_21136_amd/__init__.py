@@ -87,9 +87,9 @@ def lib() -> ctypes.CDLL:
         L.sage_diag_mfma_rate.restype = i
         L.sage_diag_mfma_rate.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.sage_decode_split_keys.restype = i
-        L.sage_decode_split_keys.argtypes = [i, i, i]
+        L.sage_decode_split_keys.argtypes = [i, i, i, i, i]
         L.sage_decode_workspace_bytes.restype = sz
-        L.sage_decode_workspace_bytes.argtypes = [i, i, i, i, i, i]
+        L.sage_decode_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
         L.sage_attn_fwd_decode.restype = i
         L.sage_attn_fwd_decode.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, f, i, i, vp, vp, sz]
         L.sage_diag_quant_kv_path.restype = i
@@ -346,21 +346,21 @@ def sage_attn_fwd_kvquantized_gqa(q, k_i8, v_fp8, k_scale, v_scale, *, causal: b
     return out
 
 
-def decode_split_keys(B: int, Hkv: int, Nk: int) -> int:
+def decode_split_keys(B: int, Hq: int, Hkv: int, Nq: int, Nk: int) -> int:
     """Keys per range that sage_attn_fwd_decode uses for split_keys = 0."""
-    return int(lib().sage_decode_split_keys(B, Hkv, Nk))
+    return int(lib().sage_decode_split_keys(B, Hq, Hkv, Nq, Nk))
 
 
-def decode_workspace_bytes(B: int, Hkv: int, Nk: int, d: int, split_keys: int = 0, rows_per_kv_head: int = 16) -> int:
-    """Workspace of sage_attn_fwd_decode; rows_per_kv_head = (Hq / Hkv) * Nq."""
-    return int(lib().sage_decode_workspace_bytes(B, Hkv, Nk, d, split_keys, rows_per_kv_head))
+def decode_workspace_bytes(B: int, Hq: int, Hkv: int, Nq: int, Nk: int, d: int, split_keys: int = 0) -> int:
+    """Workspace of sage_attn_fwd_decode."""
+    return int(lib().sage_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, split_keys))
 
 
 def sage_attn_fwd_decode(q, k_i8, v_fp8, k_scale, v_scale, *, causal: bool, sm_scale: float = 0.0,
                          p_r: float = 224.0, split_keys: int = 0, out: torch.Tensor | None = None,
                          workspace: torch.Tensor | None = None):
-    """Decode-shaped attention: q [B,Hq,Nq,d] with (Hq/Hkv)*Nq <= 64 against quantised k_i8 [B,Hkv,Nk,d] / v_fp8;
-    the keys are evaluated in ranges of split_keys keys (0: the library's choice) and combined."""
+    """Few query rows over a long quantised key sequence: q [B,Hq,Nq,d] against k_i8 [B,Hkv,Nk,d] / v_fp8; the keys
+    are evaluated in ranges of split_keys keys (0: the library's choice) and combined."""
     _dev(q, k_i8, v_fp8, k_scale, v_scale)
     B, Hq, Nq, d = q.shape
     _, Hkv, Nk, _ = k_i8.shape
@@ -369,7 +369,7 @@ def sage_attn_fwd_decode(q, k_i8, v_fp8, k_scale, v_scale, *, causal: bool, sm_s
     _dev(out)
     if out.dtype != q.dtype:
         raise SageError("out must have q's dtype")
-    need = decode_workspace_bytes(B, Hkv, Nk, d, split_keys, max(1, min(64, (Hq // max(Hkv, 1)) * Nq)))
+    need = decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, split_keys)
     ws = workspace if workspace is not None else _workspace(max(need, 256), q.device)
     _check(lib().sage_attn_fwd_decode(q.data_ptr(), k_i8.data_ptr(), v_fp8.data_ptr(), k_scale.data_ptr(),
                                       v_scale.data_ptr(), out.data_ptr(), B, Hq, Hkv, Nq, Nk, d, int(causal),

@@ -94,9 +94,9 @@ def build(verbose: bool = False) -> str:
     if bad:
         raise RuntimeError("kernels spill registers to scratch memory: " + repr(bad))
     # (the 4+8 variant at d = 128 is built for fewer wavefronts per SIMD on purpose; in the mangled name its
-    # template arguments <128, ..., Q4 = true> read "attn_kernelILi128E ... Lb1EEEv")
+    # template arguments <128, ..., Q4 = true, SPLIT = false> read "attn_kernelILi128E ... Lb1ELb0EEEv")
     def four_bit_d128(name: str) -> bool:
-        return "attn_kernelILi128E" in name and "ELb1EEEv" in name
+        return "attn_kernelILi128E" in name and "ELb1ELb0EEEv" in name
     slow = {n: u for n, u in usage.items()
             if "attn_kernel" in n and u.get("Occupancy", 0) < 4 and not four_bit_d128(n)}
     if slow:

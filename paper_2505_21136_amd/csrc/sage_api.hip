@@ -413,25 +413,31 @@ int sage_attn_fwd_kvquantized_gqa(const void *q, const int8_t *k_i8, const uint8
 /* ---- decode-shaped calls -------------------------------------------------------------------------------- */
 
 namespace {
+constexpr int kDecodeRows = 64;  // query rows per K/V head the packed decode kernel takes
 bool decode_ok(int B, int Hq, int Hkv, int Nq, int Nk, int d, int causal, int split_keys) {
-    return gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) && (Hq / Hkv) * Nq <= 64 && split_keys >= 0 &&
-           split_keys % sage::kW == 0;
+    return gqa_ok(B, Hq, Hkv, Nq, Nk, d, causal) && split_keys >= 0 && split_keys % sage::kW == 0;
 }
-int decode_steps(int B, int Hkv, int Nk, int split_keys) {
-    return split_keys > 0 ? split_keys / sage::kW : sage::decode_auto_steps_per_split(B, Hkv, Nk);
+bool packed(int Hq, int Hkv, int Nq) { return (Hq / Hkv) * Nq <= kDecodeRows; }
+int decode_steps(int B, int Hq, int Hkv, int Nq, int Nk, int split_keys) {
+    if (split_keys > 0) return split_keys / sage::kW;
+    return packed(Hq, Hkv, Nq) ? sage::decode_auto_steps_per_split(B, Hkv, Nk)
+                               : sage::ranges_auto_steps_per_split(B, Hq, Nq, Nk);
+}
+sage::DecodeScratch decode_layout(void *base, int B, int Hq, int Hkv, int Nq, int Nk, int d, int steps) {
+    return packed(Hq, Hkv, Nq)
+               ? sage::decode_scratch_layout(base, B, Hkv, Nk, d, steps, sage::cdiv((Hq / Hkv) * Nq, 16))
+               : sage::ranges_scratch_layout(base, B, Hq, Nq, Nk, d, steps);
 }
 }  // namespace
 
-int sage_decode_split_keys(int B, int Hkv, int Nk) {
-    if (B < 1 || Hkv < 1 || Nk < 1 || Nk > (1 << 22)) return 0;
-    return sage::decode_auto_steps_per_split(B, Hkv, Nk) * sage::kW;
+int sage_decode_split_keys(int B, int Hq, int Hkv, int Nq, int Nk) {
+    if (!gqa_ok(B, Hq, Hkv, Nq, Nk, 128, 0)) return 0;
+    return decode_steps(B, Hq, Hkv, Nq, Nk, 0) * sage::kW;
 }
 
-size_t sage_decode_workspace_bytes(int B, int Hkv, int Nk, int d, int split_keys, int rows_per_kv_head) {
-    if (!shape_ok(B, Hkv, Nk, d) || split_keys < 0 || split_keys % sage::kW != 0) return 0;
-    if (rows_per_kv_head < 1 || rows_per_kv_head > 64) return 0;
-    return sage::decode_scratch_layout(nullptr, B, Hkv, Nk, d, decode_steps(B, Hkv, Nk, split_keys),
-                                       sage::cdiv(rows_per_kv_head, 16)).bytes;
+size_t sage_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int d, int split_keys) {
+    if (!decode_ok(B, Hq, Hkv, Nq, Nk, d, 0, split_keys)) return 0;
+    return decode_layout(nullptr, B, Hq, Hkv, Nq, Nk, d, decode_steps(B, Hq, Hkv, Nq, Nk, split_keys)).bytes;
 }
 
 int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
@@ -443,14 +449,17 @@ int sage_attn_fwd_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
     if (!aligned16(q) || !aligned16(k_i8) || !aligned16(v_fp8) || !aligned16(v_scale) || !aligned16(out))
         return SAGE_EINVAL;
     if (!(p_r > 0.0f) || !(p_r <= 448.0f)) return SAGE_EINVAL;
-    const int steps = decode_steps(B, Hkv, Nk, split_keys);
-    const sage::DecodeScratch ws =
-        sage::decode_scratch_layout(workspace, B, Hkv, Nk, d, steps, sage::cdiv((Hq / Hkv) * Nq, 16));
+    const int steps = decode_steps(B, Hq, Hkv, Nq, Nk, split_keys);
+    const sage::DecodeScratch ws = decode_layout(workspace, B, Hq, Hkv, Nq, Nk, d, steps);
     if (!workspace || !aligned256(workspace) || workspace_bytes < ws.bytes) return SAGE_EWORKSPACE;
     sm_scale = scale_or_default(sm_scale, d);
     discard_pending_hip_error();
-    return from_hip(sage::launch_decode(q, k_i8, v_fp8, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal != 0,
-                                        sm_scale, p_r, steps, dt == SAGE_BF16, static_cast<hipStream_t>(stream), ws));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (packed(Hq, Hkv, Nq))
+        return from_hip(sage::launch_decode(q, k_i8, v_fp8, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal != 0,
+                                            sm_scale, p_r, steps, dt == SAGE_BF16, s, ws));
+    return from_hip(sage::launch_attn_ranges(q, k_i8, v_fp8, k_scale, v_scale, out, B, Hq, Hkv, Nq, Nk, d, causal != 0,
+                                             sm_scale, p_r, steps, dt == SAGE_BF16, s, ws));
 }
 
 int sage_attn_fwd_quantized(const int8_t *q_i8, const int8_t *k_i8, const uint8_t *v_fp8, const float *q_scale,

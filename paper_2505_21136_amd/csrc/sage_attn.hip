@@ -142,14 +142,22 @@ __device__ __forceinline__ void issue_tile_piece(uint8_t *dst, const uint8_t *he
 // (Its softmax part keeps the 32 exponents of a step in registers next to the scores they come from; at d = 128
 // that does not fit the 128 registers of four wavefronts per SIMD, so this one variant is built for two: one
 // workgroup per CU instead of two.)
-template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW, bool Q4>
+//
+// SPLIT (with QRAW, without Q4): the key steps are cut into `n_splits` ranges of `steps_per_split` steps and the
+// grid holds one workgroup per (head, query tile, range).  A workgroup runs the recurrence on its range alone, from
+// m = -inf, l = 0, acc = 0, and instead of O writes the range's (m, l, acc) of every row to `part_ml` / `part_acc`
+// ([item][range][128 rows][2] and [...][D] floats, item = head * tiles + tile); merge_kernel (sage_decode.hip)
+// combines the ranges.  For calls whose (head, tile) pairs alone cannot fill the GPU: few query rows over many keys.
+template <int D, int NQ, int NWAVE, int WPS, bool CAUSAL, bool BF16, bool QRAW, bool Q4, bool SPLIT = false>
 __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_kernel(
     const void *__restrict__ Qsrc, const int8_t *__restrict__ Kc, const uint8_t *__restrict__ Vt,
     const float *__restrict__ dq, const float *__restrict__ dk, const float *__restrict__ dv,
     uint16_t *__restrict__ out, Strides q_st, Strides o_st, int Nq, int Nk, int nT, int nQblk, int nKblk, int Hq,
     int group, float sm_scale, float log2_pr, int nQtiles, const float *__restrict__ q_mean,
-    const float *__restrict__ dsx) {
+    const float *__restrict__ dsx, int n_splits, int steps_per_split, float *__restrict__ part_acc,
+    float *__restrict__ part_ml) {
     static_assert(!Q4 || QRAW, "the 4+8 variant quantises Q in the kernel");
+    static_assert(!SPLIT || (QRAW && !Q4 && NQ == 1), "key ranges: unquantised Q, 8+8, one row tile per wavefront");
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types; the host pass only needs the stub
     constexpr int BM = 16 * NQ * NWAVE;  // query rows per workgroup
     constexpr int KC = D / 64;           // 64-wide contraction chunks of Q.K^T
@@ -177,10 +185,15 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
     // workgroup ids round-robin to the 8 XCDs, each with an L2 of its own: workgroup id is the `slot`-th
     // of XCD `xcd`.  Co-resident workgroups of an XCD should stream through the same K^/V^ tiles (its L2
     // then serves every fetch after the first), and a causal launch must also end on its short tiles.
-    const int n_items = (int)gridDim.x, n_qt = nQtiles, n_bh = n_items / n_qt;
+    const int n_items = (int)gridDim.x / (SPLIT ? n_splits : 1), n_qt = nQtiles, n_bh = n_items / n_qt;
     const int xcd = (int)blockIdx.x % 8, slot = (int)blockIdx.x / 8;
     int bh, qtile;  // (batch, query head), query tile
-    if (!CAUSAL && n_qt >= 128) {
+    int split = 0;  // SPLIT: this workgroup's key range (the ranges of an item are adjacent workgroup ids)
+    if constexpr (SPLIT) {
+        split = (int)blockIdx.x % n_splits;
+        bh = ((int)blockIdx.x / n_splits) / n_qt;
+        qtile = ((int)blockIdx.x / n_splits) % n_qt;
+    } else if (!CAUSAL && n_qt >= 128) {
         // a head has 16 or more tiles per XCD anyway: ids in order (query tile fastest), every XCD works
         // on the same one or two heads, and a tile missed by one L2 is likely still in the last-level cache
         bh = (int)blockIdx.x / n_qt;
@@ -237,12 +250,15 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
         }
     }
 
+    // key steps [jb, nsteps) of this workgroup (jb = 0 unless SPLIT)
     int nsteps = nT;
     if constexpr (CAUSAL) nsteps = min(Nk - 1, wg_row0 + BM - 1 + shift) / kW + 1;
+    const int jb = SPLIT ? split * steps_per_split : 0;
+    if constexpr (SPLIT) nsteps = max(jb, min(nsteps, jb + steps_per_split));  // (empty when the range lies above the rows)
     // steps this wavefront takes part in (causal: tiles entirely above its rows are skipped)
     int my_steps = nsteps;
     if constexpr (CAUSAL) my_steps = min(nsteps, (row0 + 16 * NQ - 1 + shift) / kW + 1);
-    if (row0 >= Nq) my_steps = 0;  // a wavefront without a valid row only takes part in the copies and barriers
+    if (row0 >= Nq) my_steps = jb;  // a wavefront without a valid row only takes part in the copies and barriers
     // 4+8 variant: the correction terms of this Q block, [nT][128] floats; the first wavefront copies those of
     // key step j into ds_lds[j % 3] with the K^ tile of that step (two 256-byte pieces, global -> LDS direct)
     auto copy_ds = [&](int j) {
@@ -257,9 +273,9 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
     };
     if (grp == 0) {
 #pragma unroll
-        for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[0], Kh, k_bytes, c_voff, wig, k, 0);
+        for (int k = 0; k < CPG; ++k) issue_tile_piece<D, NWG>(ldsK[jb & 1], Kh, k_bytes, c_voff, wig, k, jb);
     }
-    copy_ds(0);
+    copy_ds(jb);
 
     // the lane's B operand of S^T = K^ Q^T: 16 consecutive channels (64*ch + 16*g ..) of query row lq
     v4i qreg[NQ][KC];
@@ -403,7 +419,7 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
     };
     // matrix slot M(j): PV(j-1), then QK(j)
     auto matrix_slot = [&](int j) {
-        if (j >= 1 && j <= my_steps) {
+        if (j > jb && j <= my_steps) {
             // ---- rescale O only when some running maximum moved ----
             bool moved = false;
 #pragma unroll
@@ -453,7 +469,7 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
         // de-quantisation constants of the two K blocks of this step: every 32 steps each lane computes the
         // constants of one K block (c, and the exact split -K*c = kh + kl) and parks them in this wavefront's own
         // strip of LDS; a step then fetches its two blocks with two broadcast reads and no vector arithmetic
-        if ((j & 31) == 0) {
+        if ((j & 31) == 0 || (SPLIT && j == jb)) {
             const int blk = min(64 * (j >> 5) + lane, nKblk - 1);
             const float c = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk]);
             const float kh = -kMagicF * c;
@@ -476,9 +492,20 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
                 if constexpr (Q4)
                     alpha[qt] = softmax_step_q4<true>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], key0 + 4 * g, lim, t_lo,
                                                       t_hi, reinterpret_cast<const float4 *>(&ds_lds[j % 3][32 * g]));
-                else
+                else {
+                    const float l_old = l[qt];
                     alpha[qt] = softmax_step<true>(s[qt], c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb[qt],
                                                    key0 + 4 * g, lim, t_lo, t_hi);
+                    if constexpr (SPLIT) {
+                        // a row that has seen no key of this range yet and sees none in this step keeps its empty
+                        // state (the step's arithmetic on (-inf) - (-inf) is undefined; its P^ is zero either way);
+                        // without ranges every row sees key 0 in its first step
+                        if (lim < key0 && m[qt] == -INFINITY) {
+                            alpha[qt] = 1.0f;
+                            l[qt] = l_old;
+                        }
+                    }
+                }
             } else {
                 if constexpr (Q4)
                     alpha[qt] = softmax_step_q4<false>(s[qt], c0, c1, log2_pr, m[qt], l[qt], pb[qt], 0, 0, 8, 8,
@@ -496,7 +523,7 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
     // buffers whose last readers finished in slot 2j-1.  Every wavefront waits for its own pieces before the
     // barrier that ends slot 2j+1.
     if (grp == 0) {
-        for (int j = 0; j <= nsteps; ++j) {
+        for (int j = jb; j <= nsteps; ++j) {
             copy_k(j);  // slot 2j
             matrix_slot(j);
             __syncthreads();
@@ -506,7 +533,7 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
         }
     } else {
         __syncthreads();  // slot 0: this group idles
-        for (int j = 0; j <= nsteps; ++j) {
+        for (int j = jb; j <= nsteps; ++j) {
             copy_v(j);  // slot 2j+1
             matrix_slot(j);
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
@@ -518,6 +545,20 @@ __global__ __launch_bounds__(NWAVE * 64, (Q4 && D == 128) ? 2 : WPS) void attn_k
         }
     }
 
+    if constexpr (SPLIT) {
+        // ---- the range's (m, l, acc) of every valid row; l is the sum over the row's four lanes ----
+        const float lsum = rowgroup_sum(l[0]);
+        const int r = row0 + lq;
+        if (r < Nq) {
+            const size_t prow = (((size_t)bh * n_qt + qtile) * n_splits + split) * BM + (r - wg_row0);
+            if (g == 0) *reinterpret_cast<float2 *>(part_ml + prow * 2) = make_float2(m[0], lsum);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                *reinterpret_cast<float4 *>(part_acc + prow * D + 16 * ct + 4 * g) =
+                    make_float4(o[ct][0][0], o[ct][0][1], o[ct][0][2], o[ct][0][3]);
+        }
+        return;
+    }
     // ---- epilogue: O = acc * delta_V / (P_r * l); l already carries the factor P_r ----
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
@@ -552,7 +593,7 @@ hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8,
 #define SAGE_LAUNCH(C, BF, QR, F4)                                                                               \
     attn_kernel<D, NQ, NWAVE, WPS, C, BF, QR, F4><<<grid, NWAVE * 64, 0, stream>>>(                                \
         q, k_i8, v_fp8, q_scale, k_scale, v_scale, o16, q_st, o_st, Nq, Nk, nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
-        log2_pr, cdiv(Nq, BM), q_mean, dsx)
+        log2_pr, cdiv(Nq, BM), q_mean, dsx, 1, 0, nullptr, nullptr)
 #define SAGE_LAUNCH_Q(C, BF)                                   \
     if (q4) SAGE_LAUNCH(C, BF, true, true);                    \
     else if (q_raw) SAGE_LAUNCH(C, BF, true, false);           \
@@ -567,7 +608,42 @@ hipError_t launch_d(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8,
     return hipGetLastError();
 }
 
+// Key ranges on separate workgroups (SPLIT): grid B*Hq*tiles*S, partial results into ws (see attn_kernel).
+template <int D>
+hipError_t launch_split_d(const void *q, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                          const float *v_scale, int B, int Hq, int Hkv, int Nq, int Nk, bool causal, float sm_scale,
+                          float log2_pr, bool bf16, int n_splits, int steps_per_split, float *part_acc, float *part_ml,
+                          hipStream_t stream) {
+    const int nQt = cdiv(Nq, kBQ);
+    const dim3 grid(B * Hq * nQt * n_splits);
+    const int nT = cdiv(Nk, kW), nQ = cdiv(Nq, kBQ), nK = cdiv(Nk, kBK);
+#define SAGE_SPLIT(C, BF)                                                                                          \
+    attn_kernel<D, 1, 8, 4, C, BF, true, false, true><<<grid, 512, 0, stream>>>(                                    \
+        q, k_i8, v_fp8, nullptr, k_scale, v_scale, nullptr, q_st, q_st, Nq, Nk, nT, nQ, nK, Hq, Hq / Hkv, sm_scale, \
+        log2_pr, nQt, nullptr, nullptr, n_splits, steps_per_split, part_acc, part_ml)
+    if (causal) {
+        if (bf16) SAGE_SPLIT(true, true); else SAGE_SPLIT(true, false);
+    } else {
+        if (bf16) SAGE_SPLIT(false, true); else SAGE_SPLIT(false, false);
+    }
+#undef SAGE_SPLIT
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_attn_split(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                             const float *v_scale, int B, int Hq, int Hkv, int Nq, int Nk, int d, bool causal,
+                             float sm_scale, float p_r, bool bf16, int n_splits, int steps_per_split, float *part_acc,
+                             float *part_ml, hipStream_t stream) {
+    const float log2_pr = (float)log2((double)p_r);
+    const Strides st = contiguous_bhnd(Hq, Nq, d);
+    if (d == 128)
+        return launch_split_d<128>(q, st, k_i8, v_fp8, k_scale, v_scale, B, Hq, Hkv, Nq, Nk, causal, sm_scale, log2_pr,
+                                   bf16, n_splits, steps_per_split, part_acc, part_ml, stream);
+    return launch_split_d<64>(q, st, k_i8, v_fp8, k_scale, v_scale, B, Hq, Hkv, Nq, Nk, causal, sm_scale, log2_pr, bf16,
+                              n_splits, steps_per_split, part_acc, part_ml, stream);
+}
 
 hipError_t launch_attn(const void *q, bool q_raw, Strides q_st, const int8_t *k_i8, const uint8_t *v_fp8,
                        const float *q_scale, const float *k_scale, const float *v_scale, void *out, Strides o_st, int B,

@@ -210,7 +210,8 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
 
 // Combine the S ranges of one row: m = max_s m_s, l = sum_s 2^(m_s - m) l_s, acc likewise, then the epilogue of the
 // prefill kernel, O = acc * (delta_V / l) (l carries the factor P_r), rounded to the output type.
-// One workgroup of 256 threads per row (grid B*Hq*Nq): thread t owns channels 4*(t % (D/4)) .. +3 and the ranges
+// T > 0: the partial results come from decode_kernel (T row tiles); T = 0: from attn_kernel<..., SPLIT> (query tiles
+// of 128 rows).  One workgroup of 256 threads per row (grid B*Hq*Nq): thread t owns channels 4*(t % (D/4)) .. +3 and the ranges
 // t / (D/4), + 256/(D/4), ...; the shares are added in a fixed order through LDS, so the result does not depend on
 // timing.  (A row's ranges are read by many threads at once: with one thread walking them the launch is a chain
 // of S memory latencies.)
@@ -225,14 +226,26 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
     __shared__ float l_s[SL];
     const int row = blockIdx.x;  // (b*Hq + hq)*Nq + r
     const int r = row % Nq, bh = row / Nq, hq = bh % Hq, b = bh / Hq;
-    const int kvh = hq / group, ri = (hq % group) * Nq + r;  // row ri of the K/V head: tile ri / 16, column ri % 16
-    const int i = ri % 16;
-    // the partial results of range s sit at wavefront index w0 + s * T
-    const size_t w0 = ((size_t)b * Hkv + kvh) * S * T + ri / 16;
+    const int kvh = hq / group;
+    // where range s of this row lies: partial row index p0 + s * ps
+    size_t p0, ps;
+    if (T > 0) {
+        // decode_kernel: row ri of the K/V head sits in row tile ri / 16, column ri % 16 of wavefront
+        // ((b*Hkv + kvh)*S + s)*T + tile
+        const int ri = (hq % group) * Nq + r;
+        p0 = (((size_t)b * Hkv + kvh) * S * T + ri / 16) * 16 + ri % 16;
+        ps = (size_t)T * 16;
+    } else {
+        // attn_kernel<..., SPLIT>: row r of the head sits in query tile r / 128, row r % 128 of workgroup
+        // ((b*Hq + hq)*tiles + tile)*S + s
+        const int tiles = (Nq + kBQ - 1) / kBQ;
+        p0 = (((size_t)bh * tiles + r / kBQ) * S) * kBQ + r % kBQ;
+        ps = kBQ;
+    }
     const int tid = threadIdx.x, cq = tid % Q4, sl = tid / Q4;
     // the row's maximum over all ranges
     float mx = -INFINITY;
-    for (int s = tid; s < S; s += 256) mx = fmaxf(mx, part_ml[((w0 + (size_t)s * T) * 16 + i) * 2]);
+    for (int s = tid; s < S; s += 256) mx = fmaxf(mx, part_ml[(p0 + s * ps) * 2]);
     red[tid] = mx;
     __syncthreads();
     for (int k = 128; k >= 1; k >>= 1) {
@@ -244,8 +257,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
     for (int s = sl; s < S; s += SL) {
-        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + ((w0 + (size_t)s * T) * 16 + i) * 2);
-        const float4 a = *reinterpret_cast<const float4 *>(part_acc + ((w0 + (size_t)s * T) * 16 + i) * D + 4 * cq);
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (p0 + s * ps) * 2);
+        const float4 a = *reinterpret_cast<const float4 *>(part_acc + (p0 + s * ps) * D + 4 * cq);
         // a range in which the row saw no key has m = -inf, l = 0, acc = 0: its weight 2^(-inf) = 0 is exact
         const float wgt = __builtin_amdgcn_exp2f(ml.x - mx);
         l = __builtin_fmaf(wgt, ml.y, l);
@@ -331,6 +344,62 @@ hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
     }
 #undef SAGE_MERGE
     return hipGetLastError();
+}
+
+
+// Few workgroups, many keys (more than 64 query rows per K/V head): the prefill kernel with the key steps cut into
+// ranges on separate workgroups, then the same combination launch.
+hipError_t launch_attn_ranges(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                              const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d, bool causal,
+                              float sm_scale, float p_r, int steps_per_split, bool bf16, hipStream_t stream,
+                              const DecodeScratch &ws) {
+    const int S = ws.n_splits;
+    if (S == 1) {
+        // one range is the uncut kernel, which writes the output itself
+        const Strides st = contiguous_bhnd(Hq, Nq, d);
+        return launch_attn(q, true, st, k_i8, v_fp8, nullptr, k_scale, v_scale, out, st, B, Hq, Hkv, Nq, Nk, d, causal,
+                           sm_scale, p_r, bf16, stream);
+    }
+    hipError_t e = launch_attn_split(q, k_i8, v_fp8, k_scale, v_scale, B, Hq, Hkv, Nq, Nk, d, causal, sm_scale, p_r, bf16,
+                                     S, steps_per_split, ws.part_acc, ws.part_ml, stream);
+    if (e != hipSuccess) return e;
+    uint16_t *o16 = static_cast<uint16_t *>(out);
+    const int n_rows = B * Hq * Nq, group = Hq / Hkv;
+#define SAGE_MERGE(DD, BF) \
+    merge_kernel<DD, BF><<<n_rows, 256, 0, stream>>>(ws.part_acc, ws.part_ml, v_scale, o16, Hq, Hkv, group, Nq, S, 0)
+    if (d == 128) {
+        if (bf16) SAGE_MERGE(128, true); else SAGE_MERGE(128, false);
+    } else {
+        if (bf16) SAGE_MERGE(64, true); else SAGE_MERGE(64, false);
+    }
+#undef SAGE_MERGE
+    return hipGetLastError();
+}
+
+int ranges_auto_steps_per_split(int B, int Hq, int Nq, int Nk) {
+    // Measured (B*Hq*tiles = 16 .. 512 workgroups before the cut, 4096 .. 65536 keys): the cut pays up to 128
+    // workgroups, and best with about 512 workgroups after it (one for each of the chip's slots); from 256 workgroups
+    // on the uncut kernel is faster (every range writes 128 x (d + 2) floats per workgroup that the combination
+    // reads back).  At least four key steps per range.
+    const int nT = cdiv(Nk, kW);
+    const long items = (long)B * Hq * cdiv(Nq, kBQ);
+    if (items > 128) return nT;
+    const int want = (int)std::max<long>(1, std::min<long>(nT, 512 / items));
+    return std::max(std::min(nT, 4), cdiv(nT, want));
+}
+
+DecodeScratch ranges_scratch_layout(void *base, int B, int Hq, int Nq, int Nk, int d, int steps_per_split) {
+    const int S = cdiv(cdiv(Nk, kW), steps_per_split);
+    const size_t rows = (size_t)B * Hq * cdiv(Nq, kBQ) * S * kBQ;
+    char *p = static_cast<char *>(base);
+    DecodeScratch ws;
+    ws.n_splits = S;
+    ws.part_acc = reinterpret_cast<float *>(p);
+    size_t off = (rows * d * sizeof(float) + 255) & ~(size_t)255;
+    ws.part_ml = reinterpret_cast<float *>(p + off);
+    off += (rows * 2 * sizeof(float) + 255) & ~(size_t)255;
+    ws.bytes = off;
+    return ws;
 }
 
 }  // namespace sage

@@ -91,4 +91,18 @@ hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
                          float sm_scale, float p_r, int steps_per_split, bool bf16, hipStream_t stream,
                          const DecodeScratch &ws);
 
+// The same idea for calls with more than 64 query rows per K/V head but too few (head, query tile) pairs to fill
+// the GPU: attn_kernel with its key steps cut into ranges on separate workgroups (sage_attn.hip), then the
+// combination launch of sage_decode.hip.  Partial results: [B*Hq*tiles][S][128 rows][d] and [...][2] floats.
+hipError_t launch_attn_split(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                             const float *v_scale, int B, int Hq, int Hkv, int Nq, int Nk, int d, bool causal,
+                             float sm_scale, float p_r, bool bf16, int n_splits, int steps_per_split, float *part_acc,
+                             float *part_ml, hipStream_t stream);
+int ranges_auto_steps_per_split(int B, int Hq, int Nq, int Nk);
+DecodeScratch ranges_scratch_layout(void *base, int B, int Hq, int Nq, int Nk, int d, int steps_per_split);
+hipError_t launch_attn_ranges(const void *q, const int8_t *k_i8, const uint8_t *v_fp8, const float *k_scale,
+                              const float *v_scale, void *out, int B, int Hq, int Hkv, int Nq, int Nk, int d, bool causal,
+                              float sm_scale, float p_r, int steps_per_split, bool bf16, hipStream_t stream,
+                              const DecodeScratch &ws);
+
 }  // namespace sage

@@ -9,7 +9,7 @@ Inputs are seeded normal draws (K with a per-channel bias, as in the benchmark w
 Prints one JSON line per shape: milliseconds per call (HIP events over `--steps` calls after a warm-up) and
 attention TOPS = 4 * B * Hq * (visible query-key pairs) * d / t.
 
-With --decode the shape must be decode-shaped ((Hq/Hkv)*Nq <= 64): K and V are quantised once outside the timed
+With --decode (shapes with few query rows over many keys) K and V are quantised once outside the timed
 region (as a decode loop over a fixed cache would) and two attention-only calls are timed on them,
 sage_attn_fwd_decode (query heads packed, key ranges) and sage_attn_fwd_kvquantized_gqa (the prefill kernel on the
 same shape), with the rate at which each streams the quantised cache (2 * B * Hkv * Nk * d bytes per call).
@@ -84,7 +84,7 @@ def run_decode(shape: str, steps: int, warm_s: float) -> dict:
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(k, v, 4.5)
     del k, v
     out = torch.empty_like(q)
-    ws = torch.empty(max(256, sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, (Hq // Hkv) * Nq)), dtype=torch.uint8,
+    ws = torch.empty(max(256, sage.decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, 0)), dtype=torch.uint8,
                      device="cuda")
     sm = 1.0 / d ** 0.5
 
@@ -113,7 +113,7 @@ def run_decode(shape: str, steps: int, warm_s: float) -> dict:
         res[name] = a.elapsed_time(b) / steps
     cache_bytes = 2.0 * B * Hkv * Nk * d
     return {"shape": dict(B=B, Hq=Hq, Hkv=Hkv, Nq=Nq, Nk=Nk, d=d, causal=causal, dtype=str(dtype).split(".")[-1]),
-            "split_keys": sage.decode_split_keys(B, Hkv, Nk),
+            "split_keys": sage.decode_split_keys(B, Hq, Hkv, Nq, Nk),
             "decode_ms": round(res["decode"], 4), "prefill_kernel_ms": round(res["prefill_kernel"], 4),
             "decode_cache_GBps": round(cache_bytes / (res["decode"] * 1e-3) / 1e9, 1),
             "prefill_kernel_cache_GBps": round(cache_bytes / (res["prefill_kernel"] * 1e-3) / 1e9, 1)}

@@ -98,21 +98,24 @@ def test_argument_checks_return_codes_without_touching_the_gpu():
 def test_decode_helpers_and_argument_checks_on_the_host():
     """Range length, workspace size and the argument checks of the decode entry point are host arithmetic."""
     L = sage.lib()
-    for B, Hkv, Nk in ((8, 8, 32768), (1, 8, 131072), (64, 8, 4096), (1, 1, 1), (2, 3, 129), (4096, 8, 1024)):
-        sk = sage.decode_split_keys(B, Hkv, Nk)
+    for B, Hq, Hkv, Nq, Nk in ((8, 32, 8, 1, 32768), (1, 32, 8, 1, 131072), (64, 32, 8, 1, 4096), (1, 1, 1, 1, 1),
+                               (2, 6, 3, 5, 129), (4096, 8, 8, 1, 1024), (1, 8, 2, 128, 32768), (2, 4, 4, 1000, 9000)):
+        sk = sage.decode_split_keys(B, Hq, Hkv, Nq, Nk)
         nT = -(-Nk // 128)
         assert sk % 128 == 0 and 128 <= sk <= max(128, nT * 128)
         ranges = -(-nT // (sk // 128))
-        assert ranges >= 1 and (nT < 2 or sk >= 256)           # at least two key steps per wavefront
-        assert B * Hkv * ranges <= max(B * Hkv, 2 * 1024 + B * Hkv)   # not many more wavefronts than asked for
+        packed = (Hq // Hkv) * Nq <= 64
+        units = B * Hkv if packed else B * Hq * -(-Nq // 128)       # wavefronts (row tiles aside) or workgroups
+        assert ranges >= 1 and (nT < 2 or sk >= 256)                # at least two key steps per range
+        assert units * ranges <= max(units, 2 * 1024 + units)       # not many more than asked for
         for d in (64, 128):
-            one = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 16)
-            four = sage.decode_workspace_bytes(B, Hkv, Nk, d, 0, 64)
-            assert one % 256 == 0 and one >= B * Hkv * ranges * 16 * (d + 2) * 4 and four >= 4 * one - 3 * 512
-            assert sage.decode_workspace_bytes(B, Hkv, Nk, d, sk, 16) == one
-    assert sage.decode_workspace_bytes(1, 1, 1024, 128, 100, 16) == 0      # not a multiple of 128
-    assert sage.decode_workspace_bytes(1, 1, 1024, 128, 128, 65) == 0      # more rows than the path takes
-    assert sage.decode_workspace_bytes(1, 1, 1024, 96, 128, 16) == 0
+            ws = sage.decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, 0)
+            rows = B * Hkv * ranges * 16 * -(-(Hq // Hkv) * Nq // 16) if packed else units * ranges * 128
+            assert ws % 256 == 0 and rows * (d + 2) * 4 <= ws <= rows * (d + 2) * 4 + 512
+            assert sage.decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, sk) == ws
+    assert sage.decode_workspace_bytes(1, 1, 1, 1, 1024, 128, 100) == 0      # not a multiple of 128
+    assert sage.decode_workspace_bytes(1, 3, 2, 1, 1024, 128, 128) == 0      # Hq not a multiple of Hkv
+    assert sage.decode_workspace_bytes(1, 1, 1, 1, 1024, 96, 128) == 0
     buf = (ctypes.c_char * 4096)()
     p = (ctypes.addressof(buf) + 255) & ~255                    # never dereferenced: the checks fail first
     EINVAL, EWS = -1, -2
@@ -121,7 +124,7 @@ def test_decode_helpers_and_argument_checks_on_the_host():
         return L.sage_attn_fwd_decode(q, p, p, p, p, p, 1, Hq, Hkv, Nq, Nk, d, causal, 0.0, p_r, split, dt, None, ws, wsb)
 
     assert dec() == EWS                                         # a valid call reaches the workspace check
-    assert dec(Nq=16) == EWS and dec(Nq=17) == EINVAL           # (8/2)*16 = 64 rows per K/V head is the limit
+    assert dec(Nq=16) == EWS and dec(Nq=17) == EWS              # 64 rows per K/V head packed, more on the prefill kernel
     assert dec(Hq=6, Hkv=4) == EINVAL                           # Hq not a multiple of Hkv
     assert dec(split=100) == EINVAL and dec(split=-128) == EINVAL and dec(split=256) == EWS
     assert dec(Nq=4, Nk=3, causal=1) == EINVAL                  # the end-aligned mask needs Nk >= Nq

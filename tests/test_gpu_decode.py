@@ -62,6 +62,9 @@ ONE_RANGE = [  # idx, B, Hq, Hkv, Nq, Nk, d, causal
     # more than 16 rows per K/V head: several row tiles, heads that straddle them
     (2, 2, 8, 2, 5, 600, 128, True), (3, 1, 4, 1, 16, 1000, 64, True), (5, 1, 16, 2, 3, 257, 128, False),
     (1, 2, 2, 2, 33, 400, 128, True),
+    # more than 64 rows per K/V head: the prefill kernel with key ranges (here: one range)
+    (2, 1, 8, 2, 17, 700, 128, True), (3, 2, 2, 2, 130, 600, 64, True), (5, 1, 4, 1, 300, 300, 128, True),
+    (1, 1, 2, 2, 200, 1000, 128, False),
 ]
 
 
@@ -82,12 +85,15 @@ RANGES = [  # idx, B, Hq, Hkv, Nq, Nk, d, causal, split_keys (0: the library's c
     (5, 4, 8, 1, 2, 777, 128, True, 128), (5, 8, 4, 4, 16, 300, 128, True, 128),
     (1, 8, 4, 2, 8, 129, 64, True, 128),
     (2, 2, 8, 2, 5, 1500, 128, True, 256), (4, 2, 4, 1, 16, 2000, 64, True, 0), (5, 1, 24, 3, 7, 900, 128, False, 384),
+    # more than 64 rows per K/V head: key ranges on the prefill kernel, rows that see nothing of the last ranges
+    (2, 1, 8, 2, 40, 3000, 128, True, 512), (3, 2, 4, 4, 129, 2500, 64, True, 0), (5, 1, 2, 1, 256, 4096, 128, False, 1024),
+    (1, 1, 4, 2, 700, 1900, 128, True, 256), (4, 1, 2, 2, 100, 5000, 64, False, 0),
 ]
 
 
 @pytest.mark.parametrize("idx,B,Hq,Hkv,Nq,Nk,d,causal,split_keys", RANGES)
 def test_ranges_against_the_oracle_on_the_same_ranges(idx, B, Hq, Hkv, Nq, Nk, d, causal, split_keys):
-    used = split_keys or sage.decode_split_keys(B, Hkv, Nk)
+    used = split_keys or sage.decode_split_keys(B, Hq, Hkv, Nq, Nk)
     say(f"[decode] ranges of {used}: cfg{idx} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} causal={causal}")
     assert used % 128 == 0 and used >= 128
     q, k, v, sm = _inputs(idx, B, Hq, Hkv, Nq, Nk, d)
@@ -116,7 +122,7 @@ def _random_case(seed):
 @pytest.mark.parametrize("seed", range(24))
 def test_seeded_random_decode_shapes(seed):
     idx, B, Hq, Hkv, Nq, Nk, d, causal, split_keys = _random_case(seed)
-    used = split_keys or sage.decode_split_keys(B, Hkv, Nk)
+    used = split_keys or sage.decode_split_keys(B, Hq, Hkv, Nq, Nk)
     say(f"[decode] seed {seed}: cfg{idx} B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} d{d} causal={causal} ranges of {used}")
     q, k, v, sm = _inputs(idx, B, Hq, Hkv, Nq, Nk, d)
     out, _ = _gpu(q, k, v, causal, sm, split_keys)
@@ -137,7 +143,7 @@ def test_decode_call_can_be_replayed_from_a_hip_graph():
     q, k, v, sm = _inputs(2, B, Hq, Hkv, Nq, Nk, d)
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
-    ws = torch.empty(sage.decode_workspace_bytes(B, Hkv, Nk, d, 256, (Hq // Hkv) * Nq), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sage.decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, d, 256), dtype=torch.uint8, device=DEV)
     out = torch.empty_like(qd)
     eager = sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm, split_keys=256,
                                       workspace=ws).clone()
@@ -173,7 +179,7 @@ def test_long_cache_with_the_library_split():
     """The shape the path is for: B 8, 32 / 8 heads, one query row over 32768 keys; all heads of two K/V heads
     against the oracle."""
     B, Hq, Hkv, Nq, Nk, d = 8, 32, 8, 1, 32768, 128
-    used = sage.decode_split_keys(B, Hkv, Nk)
+    used = sage.decode_split_keys(B, Hq, Hkv, Nq, Nk)
     say(f"[decode] long cache, ranges of {used}")
     q, k, v, sm = _inputs(5, B, Hq, Hkv, Nq, Nk, d)
     out, _ = _gpu(q, k, v, True, sm, 0)
@@ -189,11 +195,11 @@ def test_long_cache_with_the_library_split():
 
 
 def test_argument_errors():
-    q, k, v, sm = _inputs(1, 1, 16, 2, 9, 256, 128)       # (16/2)*9 = 72 rows per K/V head
+    q, k, v, sm = _inputs(1, 1, 4, 2, 9, 8, 128)          # causal with more query rows than keys
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
     with pytest.raises(sage.SageError):
-        sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=False, sm_scale=sm)
+        sage.sage_attn_fwd_decode(qd, k_i8, v_fp8, k_scale, v_scale, causal=True, sm_scale=sm)
     q, k, v, sm = _inputs(1, 1, 4, 2, 1, 256, 128)
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
     k_i8, k_scale, _, v_fp8, v_scale = sage.sage_quant_kv(kd, vd, 4.5)
