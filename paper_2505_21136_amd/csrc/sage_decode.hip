@@ -25,8 +25,10 @@ namespace {
 
 // D: head dimension; CAUSAL: end-aligned mask (key n visible to row r iff n <= r + Nk - Nq); BF16: type of Q / O.
 // Grid: ceil(B*Hkv*S*T / 4) workgroups of 4 wavefronts; wavefront w = ((b*Hkv + kvh)*S + split)*T + row tile.
-template <int D, bool CAUSAL, bool BF16>
-__global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restrict__ Q, const int8_t *__restrict__ Kc,
+// NT: row tiles per wavefront (1: up to 16 rows per K/V head, 2 wavefronts per SIMD; 2: up to 32 rows per
+// wavefront -- the operands of a key step are fetched once for both tiles --, 1 wavefront per SIMD).
+template <int D, bool CAUSAL, bool BF16, int NT>
+__global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void decode_kernel(const uint16_t *__restrict__ Q, const int8_t *__restrict__ Kc,
                                                         const uint8_t *__restrict__ Vt, const float *__restrict__ dk,
                                                         float *__restrict__ part_acc, float *__restrict__ part_ml,
                                                         int n_waves, int Hq, int Hkv, int group, int Nq, int Nk, int nT,
@@ -39,26 +41,33 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
     const int w = __builtin_amdgcn_readfirstlane((int)blockIdx.x * 4 + (int)(threadIdx.x >> 6));
     if (w >= n_waves) return;  // (whole wavefronts leave; the kernel has no barrier)
     const int lq = lane & 15, g = lane >> 4;
-    const int rt = w % T, split = (w / T) % S, bhk = w / (T * S);
+    // T row tiles in groups of NT per wavefront: TW = ceil(T / NT) wavefronts per (K/V head, range)
+    const int TW = (T + NT - 1) / NT;
+    const int rt0 = (w % TW) * NT, split = (w / TW) % S, bhk = w / (TW * S);
     const int b = bhk / Hkv, kvh = bhk % Hkv;
     const int R = group * Nq;  // rows in use (<= 16 * T)
-    // row 16*rt + lq of the K/V head = query row r of query head hq (rows past R repeat row 0 of head 0 and are
-    // never stored)
-    const int ri = 16 * rt + lq;
-    const bool row_ok = ri < R;
-    const int hq = kvh * group + (row_ok ? ri / Nq : 0);
-    const int r = row_ok ? ri % Nq : 0;
     const int shift = Nk - Nq;
 
     const int8_t *Kh = Kc + (size_t)bhk * Nk * D;
     const uint8_t *Vh = Vt + (size_t)bhk * nT * D * 128;
     const int j0 = split * steps_per_split, j1 = min(nT, j0 + steps_per_split);
 
-    // ---- Q: load 16-bit, quantise per head over its Nq rows (the stand-alone quantiser's binary32 steps on one
-    // block of Nq <= 64 rows: a head's rows are one Q quantisation block), straight into the B operand layout of the INT8 MFMA ----
-    v4i qreg[KC];
-    float delta_q;
-    {
+    // per row tile: row 16*(rt0 + qt) + lq of the K/V head = query row r of query head hq (rows past R repeat row 0
+    // of head 0 and are never stored)
+    bool row_ok[NT];
+    int lim[NT];
+    v4i qreg[NT][KC];
+    double cq[NT];
+#pragma unroll
+    for (int qt = 0; qt < NT; ++qt) {
+        const int ri = 16 * (rt0 + qt) + lq;
+        row_ok[qt] = ri < R;
+        const int hq = kvh * group + (row_ok[qt] ? ri / Nq : 0);
+        const int r = row_ok[qt] ? ri % Nq : 0;
+        lim[qt] = CAUSAL ? min(Nk - 1, r + shift) : Nk - 1;  // last visible key of this lane's row
+        // ---- Q: load 16-bit, quantise per head over its Nq rows (the stand-alone quantiser's binary32 steps on
+        // one block of Nq <= 64 rows: a head's rows are one Q quantisation block), straight into the B operand
+        // layout of the INT8 MFMA ----
         const uint16_t *Qr = Q + (((size_t)b * Hq + hq) * Nq + r) * D;
         uint4 qraw[KC][2];
         float amax = 0.0f;
@@ -89,9 +98,9 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
                 }
         }
         float a = rowgroup_max(amax);
-        if (!row_ok) a = 0.0f;
+        if (!row_ok[qt]) a = 0.0f;
         const float rcp = a > 0.0f ? 127.0f / a : 0.0f;
-        delta_q = a / 127.0f;
+        cq[qt] = (double)(a / 127.0f) * (double)sm_scale * 1.4426950408889634;
 #pragma unroll
         for (int ch = 0; ch < KC; ++ch)
 #pragma unroll
@@ -109,22 +118,25 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
                     }
                     const uint32_t lo2 = __builtin_amdgcn_perm(cb[1], cb[0], 0x0c0c0400u);
                     const uint32_t hi2 = __builtin_amdgcn_perm(cb[3], cb[2], 0x0c0c0400u);
-                    qreg[ch][2 * h + hh] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
+                    qreg[qt][ch][2 * h + hh] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
                 }
             }
     }
-    const double cq = (double)delta_q * (double)sm_scale * 1.4426950408889634;
     const v4i cinit = {kMagic, kMagic, kMagic, kMagic};
 
-    // last visible key of this lane's row, and of the first / last row in use
-    const int lim = CAUSAL ? min(Nk - 1, r + shift) : Nk - 1;
+    // last visible key of the first / last row in use
     const int lim_min = CAUSAL ? min(Nk - 1, shift) : Nk - 1;
     const int lim_max = Nk - 1;
 
-    float m = -INFINITY, l = 0.0f;
-    v4f o[CT];
+    float m[NT], l[NT];
+    v4f o[NT][CT];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) o[ct] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int qt = 0; qt < NT; ++qt) {
+        m[qt] = -INFINITY;
+        l[qt] = 0.0f;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) o[qt][ct] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
 
     // K^ operand of step j: rows 16t + lq, 16-byte chunk 4ch + g (rows past the end are read from the last row
     // and masked)
@@ -150,60 +162,70 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(const uint16_t *__restri
             va[ct][0] = *reinterpret_cast<const v4i *>(vr + g * 16);
             va[ct][1] = *reinterpret_cast<const v4i *>(vr + (4 + g) * 16);
         }
-        // ---- S^T = K^ Q^T ----
-        v4i s[8];
-#pragma unroll
-        for (int ch = 0; ch < KC; ++ch)
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-                s[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka[ch][t], qreg[ch], ch == 0 ? cinit : s[t], 0, 0, 0);
-        if (j + 1 < j1) load_k(j + 1);
-
-        // ---- softmax step: every lane has the constants of its own row (its head's delta_Q) ----
-        const int blk0 = min(2 * j, nKblk - 1), blk1 = min(2 * j + 1, nKblk - 1);
-        const float c0 = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk0]);
-        const float c1 = (float)(cq * (double)dk[(size_t)bhk * nKblk + blk1]);
-        const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;
-        const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
-        v8i pb;
-        float alpha;
+        const float dk0 = dk[(size_t)bhk * nKblk + min(2 * j, nKblk - 1)];
+        const float dk1 = dk[(size_t)bhk * nKblk + min(2 * j + 1, nKblk - 1)];
         const bool masked_step = (key0 + kW > Nk) || (CAUSAL && key0 + kW - 1 > lim_min);
-        if (masked_step) {
-            const int t_lo = min(8, max(0, (lim_min - key0 + 1) >> 4));
-            const int t_hi = min(8, max(0, ((lim_max - key0) >> 4) + 1));
-            const float l_old = l;
-            alpha = softmax_step<true>(s, c0, c1, kh0, kh1, kl0, kl1, log2_pr, m, l, pb, key0 + 4 * g, lim, t_lo, t_hi);
-            // a row that has seen no key yet and sees none in this step keeps its empty state (the step's
-            // arithmetic on (-inf) - (-inf) is undefined; its P^ is zero either way)
-            if (lim < key0 && m == -INFINITY) {
-                alpha = 1.0f;
-                l = l_old;
-            }
-        } else {
-            alpha = softmax_step<false>(s, c0, c1, kh0, kh1, kl0, kl1, log2_pr, m, l, pb, 0, 0, 8, 8);
-        }
+        const int t_lo = min(8, max(0, (lim_min - key0 + 1) >> 4));
+        const int t_hi = min(8, max(0, ((lim_max - key0) >> 4) + 1));
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) {
+            // ---- S^T = K^ Q^T ----
+            v4i s[8];
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch)
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    s[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka[ch][t], qreg[qt][ch], ch == 0 ? cinit : s[t], 0, 0, 0);
+            if (qt == NT - 1 && j + 1 < j1) load_k(j + 1);
 
-        // ---- O^T = alpha O^T + V^T P^T ----
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+            // ---- softmax step: every lane has the constants of its own row (its head's delta_Q) ----
+            const float c0 = (float)(cq[qt] * (double)dk0), c1 = (float)(cq[qt] * (double)dk1);
+            const float kh0 = -kMagicF * c0, kh1 = -kMagicF * c1;
+            const float kl0 = __builtin_fmaf(-kMagicF, c0, -kh0), kl1 = __builtin_fmaf(-kMagicF, c1, -kh1);
+            v8i pb;
+            float alpha;
+            if (masked_step) {
+                const float l_old = l[qt];
+                alpha = softmax_step<true>(s, c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb, key0 + 4 * g, lim[qt],
+                                           t_lo, t_hi);
+                // a row that has seen no key yet and sees none in this step keeps its empty state (the step's
+                // arithmetic on (-inf) - (-inf) is undefined; its P^ is zero either way)
+                if (lim[qt] < key0 && m[qt] == -INFINITY) {
+                    alpha = 1.0f;
+                    l[qt] = l_old;
+                }
+            } else {
+                alpha = softmax_step<false>(s, c0, c1, kh0, kh1, kl0, kl1, log2_pr, m[qt], l[qt], pb, 0, 0, 8, 8);
+            }
+
+            // ---- O^T = alpha O^T + V^T P^T ----
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) o[ct] *= alpha;
-        }
+                for (int ct = 0; ct < CT; ++ct) o[qt][ct] *= alpha;
+            }
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const v8i a = {va[ct][0][0], va[ct][0][1], va[ct][0][2], va[ct][0][3],
-                           va[ct][1][0], va[ct][1][1], va[ct][1][2], va[ct][1][3]};
-            o[ct] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, pb, o[ct], 0, 0, 0, 0, 0, 0);
+            for (int ct = 0; ct < CT; ++ct) {
+                const v8i a = {va[ct][0][0], va[ct][0][1], va[ct][0][2], va[ct][0][3],
+                               va[ct][1][0], va[ct][1][1], va[ct][1][2], va[ct][1][3]};
+                o[qt][ct] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, pb, o[qt][ct], 0, 0, 0, 0, 0, 0);
+            }
         }
     }
 
-    // ---- this range's (m, l, acc) of every row in use; l is the sum over the row's four lanes ----
-    const float lsum = rowgroup_sum(l);
-    if (row_ok) {
-        if (g == 0) *reinterpret_cast<float2 *>(part_ml + ((size_t)w * 16 + lq) * 2) = make_float2(m, lsum);
-        float *pa = part_acc + ((size_t)w * 16 + lq) * D;
+    // ---- this range's (m, l, acc) of every row in use; l is the sum over the row's four lanes.  Partial rows are
+    // indexed (((b*Hkv + kvh)*S + split)*T + row tile)*16 + lq ----
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-            *reinterpret_cast<float4 *>(pa + 16 * ct + 4 * g) = make_float4(o[ct][0], o[ct][1], o[ct][2], o[ct][3]);
+    for (int qt = 0; qt < NT; ++qt) {
+        const float lsum = rowgroup_sum(l[qt]);
+        if (row_ok[qt]) {
+            const size_t prow = (((size_t)bhk * S + split) * T + rt0 + qt) * 16 + lq;
+            if (g == 0) *reinterpret_cast<float2 *>(part_ml + prow * 2) = make_float2(m[qt], lsum);
+            float *pa = part_acc + prow * D;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                *reinterpret_cast<float4 *>(pa + 16 * ct + 4 * g) =
+                    make_float4(o[qt][ct][0], o[qt][ct][1], o[qt][ct][2], o[qt][ct][3]);
+        }
     }
 #endif  // __HIP_DEVICE_COMPILE__
 }
@@ -318,14 +340,22 @@ hipError_t launch_decode(const void *q, const int8_t *k_i8, const uint8_t *v_fp8
     const int nT = cdiv(Nk, kW), nK = cdiv(Nk, kBK);
     const int S = ws.n_splits;
     const int T = cdiv(group * Nq, 16);
-    const int n_waves = B * Hkv * S * T;
+    const int nt = T >= 2 ? 2 : 1;  // row tiles per wavefront (measured: 0.16 against 0.25 ms at 64 rows per K/V head, B 8, 32768 keys)
+    const int n_waves = B * Hkv * S * cdiv(T, nt);
     const float log2_pr = (float)log2((double)p_r);
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     uint16_t *o16 = static_cast<uint16_t *>(out);
-#define SAGE_DEC(DD, C, BF)                                                                                          \
-    decode_kernel<DD, C, BF><<<cdiv(n_waves, 4), 256, 0, stream>>>(q16, k_i8, v_fp8, k_scale, ws.part_acc, ws.part_ml, \
-                                                                   n_waves, Hq, Hkv, group, Nq, Nk, nT, nK, S, T,    \
-                                                                   steps_per_split, sm_scale, log2_pr)
+#define SAGE_DEC(DD, C, BF)                                                                                       \
+    do {                                                                                                          \
+        if (nt == 1)                                                                                              \
+            decode_kernel<DD, C, BF, 1><<<cdiv(n_waves, 4), 256, 0, stream>>>(                                     \
+                q16, k_i8, v_fp8, k_scale, ws.part_acc, ws.part_ml, n_waves, Hq, Hkv, group, Nq, Nk, nT, nK, S, T, \
+                steps_per_split, sm_scale, log2_pr);                                                              \
+        else                                                                                                      \
+            decode_kernel<DD, C, BF, 2><<<cdiv(n_waves, 4), 256, 0, stream>>>(                                     \
+                q16, k_i8, v_fp8, k_scale, ws.part_acc, ws.part_ml, n_waves, Hq, Hkv, group, Nq, Nk, nT, nK, S, T, \
+                steps_per_split, sm_scale, log2_pr);                                                              \
+    } while (0)
     if (d == 128) {
         if (causal) { if (bf16) SAGE_DEC(128, true, true); else SAGE_DEC(128, true, false); }
         else        { if (bf16) SAGE_DEC(128, false, true); else SAGE_DEC(128, false, false); }
